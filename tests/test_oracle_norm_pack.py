@@ -1,0 +1,160 @@
+"""Pins for the oracle's pack/unpack index map and its global gradient norm.
+
+Chunks are fixed-size flat buffers that hold the model states (paper,
+"Hierarchical Chunk Management for Model States"); the dense layout packs the
+tensors in declaration order and pads only the last chunk.  The norm is the
+global L2 norm of the unscaled gradients (textbook global-norm clipping; the
+paper does not define it).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2406_08334_amd import shapes, synth
+
+
+def bf16_words(x):
+    return torch.tensor(x, dtype=torch.float32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def fp16_words(x):
+    return np.asarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+# ----------------------------------------------------------------- pack / unpack
+
+@pytest.mark.parametrize("S", [8, 16])
+def test_pack_matches_per_element_brute_force(orc, S):
+    rng = np.random.default_rng(1)
+    sizes = [1, 3, 7, 8, 9, 17]
+    tensors = [rng.integers(0, 1 << 16, size=n, dtype=np.uint16) for n in sizes]
+    chunks = orc.pack_dense(tensors, S)
+    flat = np.concatenate(tensors)
+    C = -(-flat.size // S)
+    assert chunks.shape == (C, S)
+    for e in range(flat.size):                      # the definition, element by element
+        assert chunks[e // S, e % S] == flat[e]
+    for e in range(flat.size, C * S):               # padding
+        assert chunks[e // S, e % S] == 0
+    back = orc.unpack_dense(chunks, sizes)
+    for a, b in zip(tensors, back):
+        assert np.array_equal(a, b)
+
+
+def test_pack_round_trip_keeps_special_bit_patterns(orc):
+    special = np.array([0x0000, 0x8000, 0x0001, 0x8001, 0x7F80, 0xFF80, 0x7FC0, 0x7FA5, 0xFFFF,
+                        0x7C00, 0xFC00, 0x7E01, 0x03FF, 0x0400], dtype=np.uint16)
+    tensors = [special[:5].copy(), special[5:6].copy(), special[6:].copy()]
+    chunks = orc.pack_dense(tensors, 4)
+    assert np.array_equal(chunks.reshape(-1)[:special.size], special)
+    assert np.all(chunks.reshape(-1)[special.size:] == 0)
+    back = orc.unpack_dense(chunks, [t.size for t in tensors])
+    assert all(np.array_equal(a, b) for a, b in zip(tensors, back))
+
+
+def test_pack_gpt2_block_worked_example(orc):
+    # Sizes of one GPT-2 block with hidden 768, chunks of 2^22 elements.
+    table, S = shapes.workload("gpt2_block_768")
+    sizes = [n for _, n in table]
+    assert sum(sizes) == 7_087_872 and S == 4_194_304
+    start = dict(zip([k for k, _ in table], np.cumsum([0] + sizes[:-1]).tolist()))
+    # ln1 (2*768) + qkv (768*2304 + 2304) + proj (768*768 + 768) + ln2 (2*768) = 2,365,440
+    assert start["h0.mlp.c_fc.weight"] == 2_365_440
+    assert start["h0.mlp.c_fc.weight"] + 768 * 3072 == 4_724_736      # straddles 4,194,304
+    tensors = [np.full(n, i + 1, dtype=np.uint16) for i, n in enumerate(sizes)]
+    chunks = orc.pack_dense(tensors, S)
+    assert chunks.shape == (2, S)
+    assert chunks[0, S - 1] == 9 and chunks[1, 0] == 9                 # c_fc.weight on both sides
+    assert chunks[1, 4_724_736 - S - 1] == 9 and chunks[1, 4_724_736 - S] == 10
+    pad = 2 * S - sum(sizes)
+    assert pad == 1_300_736 and np.all(chunks[1, S - pad:] == 0) and chunks[1, S - pad - 1] == 12
+
+
+def test_chunk_counts_of_the_workloads():
+    want = {"gpt2_block_768": (7_087_872, 2), "gpt2_xl": (1_557_611_200, 47),
+            "llama_7b": (6_738_415_616, 101), "llama_13b": (13_015_864_320, 194)}
+    for name, (n, c) in want.items():
+        table, S = shapes.workload(name)
+        assert shapes.total_elems(table) == n and shapes.n_chunks(table, S) == c
+
+
+# ----------------------------------------------------------------------- norm
+
+def test_sqnorm_matches_fsum_brute_force(orc):
+    rng = np.random.default_rng(3)
+    for dt, to_words in ((orc.BF16, bf16_words), (orc.FP16, fp16_words)):
+        x = rng.normal(0, 1e-3, size=1000).astype(np.float32)
+        w = to_words(x)
+        vals = orc.decode16(w, dt).astype(np.float64)
+        want = math.fsum((vals * vals).tolist())     # squares of 16-bit values are exact in fp64
+        got = orc.sqnorm(w, dt)
+        assert abs(got - want) <= 1e-13 * want
+        got4 = orc.sqnorm(w, dt, loss_scale=4.0, block=64, threads=3)
+        assert abs(got4 - want / 16.0) <= 1e-13 * want / 16.0
+
+
+def test_sqnorm_closed_forms(orc):
+    ones = np.full(1 << 22, 0x3F80, dtype=np.uint16)            # bf16 1.0
+    assert math.sqrt(orc.sqnorm(ones, orc.BF16, block=1 << 20, threads=4)) == 2048.0
+    z = np.zeros(1000, dtype=np.uint16)
+    assert orc.sqnorm(z, orc.BF16) == 0.0
+    assert orc.clip_coef(0.0, 1.0) == 1.0
+    one = np.zeros(77, dtype=np.uint16)
+    one[41] = bf16_words([-0.375])[0]
+    assert math.sqrt(orc.sqnorm(one, orc.BF16)) == 0.375
+    assert orc.sqnorm(np.zeros(0, dtype=np.uint16), orc.BF16) == 0.0
+
+
+def test_sqnorm_power_of_two_scaling_is_exact(orc):
+    rng = np.random.default_rng(5)
+    x = rng.normal(0, 1e-3, size=4096).astype(np.float32)
+    w = bf16_words(x)
+    w8 = bf16_words(orc.decode16(w, orc.BF16) * 8.0)
+    a, b = orc.sqnorm(w, orc.BF16, block=512), orc.sqnorm(w8, orc.BF16, block=512)
+    assert b == 64.0 * a
+    # loss scale 8 undoes it exactly
+    assert orc.sqnorm(w8, orc.BF16, loss_scale=8.0, block=512) == a
+
+
+def test_sqnorm_block_and_thread_invariance(orc):
+    g = synth.as_u16(synth.normal_16(synth.SEED_GRADS, 1, 0, 0, 300_001, 1e-3, torch.bfloat16, "cpu"))
+    ref = orc.sqnorm(g, orc.BF16)
+    for block in (8, 1000, 1 << 16):
+        a = orc.sqnorm(g, orc.BF16, block=block, threads=1)
+        b = orc.sqnorm(g, orc.BF16, block=block, threads=5)
+        assert a == b                                 # threads never change the bits
+        assert abs(a - ref) <= 1e-12 * ref            # block size only moves the last bits
+
+
+def test_norm_of_synthetic_grads_is_sigma_sqrt_n(orc):
+    n = 7_087_872
+    g = synth.as_u16(synth.normal_16(synth.SEED_GRADS, 1, 0, 0, n, 1e-3, torch.bfloat16, "cpu"))
+    norm = math.sqrt(orc.sqnorm(g, orc.BF16, block=1 << 22, threads=8))
+    assert abs(norm - 1e-3 * math.sqrt(n)) < 2e-3 * 2.662     # ~2.662
+    assert abs(orc.clip_coef(norm, 1.0) - 1.0 / (norm + 1e-6)) < 1e-15
+
+
+def test_clip_coef(orc):
+    assert orc.clip_coef(0.5, 1.0) == 1.0
+    assert orc.clip_coef(4.0, 1.0) == 1.0 / (4.0 + 1e-6)
+    assert orc.clip_coef(4.0, 0.0) == 1.0 and orc.clip_coef(4.0, -1.0) == 1.0
+    assert orc.clip_coef(1e30, 2.0) == 2.0 / (1e30 + 1e-6)
+
+
+def test_found_nonfinite(orc):
+    g = bf16_words(np.linspace(-1, 1, 100))
+    assert not orc.found_nonfinite(g, orc.BF16)
+    for pat in (0x7F80, 0xFF80, 0x7FC0, 0x7F81):
+        h = g.copy(); h[37] = pat
+        assert orc.found_nonfinite(h, orc.BF16)
+    h = g.copy(); h[5] = 0x7F7F                       # largest finite bf16
+    assert not orc.found_nonfinite(h, orc.BF16)
+    f = fp16_words(np.linspace(-1, 1, 100))
+    assert not orc.found_nonfinite(f, orc.FP16)
+    for pat in (0x7C00, 0xFC00, 0x7E00, 0x7C01):
+        h = f.copy(); h[99] = pat
+        assert orc.found_nonfinite(h, orc.FP16)
+    h = f.copy(); h[0] = 0x7BFF                       # 65504
+    assert not orc.found_nonfinite(h, orc.FP16)

@@ -1,0 +1,51 @@
+"""Scale-aware reading of "relative 1e-6" for the fp32 state arrays.
+
+m, v and w are sums of terms; where terms of opposite sign cancel, the plain
+relative error of a correctly computed fp32 value is unbounded.  The tolerance is
+therefore applied against the accumulated MAGNITUDE of the terms that formed the
+value, tracked in fp64 beside the trajectory:
+
+  A_t = beta1 A_{t-1} + (1-beta1) |g_t|          (scale of m;  A_0 = |m_0|)
+  v itself                                        (scale of v: all terms >= 0)
+  W_t = W_{t-1} (1 - lr wd) + step_t A_t / d_t    (scale of w;  W_0 = |w_0|)
+
+with g_t the clipped, unscaled gradient, step_t = lr/(1-beta1^t) and
+d_t = sqrt(v_t)/sqrt(1-beta2^t) + eps.  Away from cancellation A = |m| and
+W ~ |w|, i.e. this is the plain relative error.
+"""
+import numpy as np
+
+
+class ScaleTracker:
+    def __init__(self, w0, m0, hp):
+        self.A = np.abs(np.asarray(m0, dtype=np.float64))
+        self.W = np.abs(np.asarray(w0, dtype=np.float64))
+        self.hp = hp
+
+    def advance(self, t, g_eff, v_new):
+        """g_eff: fp64 clipped+unscaled gradient of update t; v_new: v after update t."""
+        hp = self.hp
+        self.A = hp["beta1"] * self.A + (1.0 - hp["beta1"]) * np.abs(g_eff)
+        step = hp["lr"] / (1.0 - hp["beta1"] ** t)
+        d = np.sqrt(np.asarray(v_new, dtype=np.float64)) / np.sqrt(1.0 - hp["beta2"] ** t) + hp["eps"]
+        self.W = self.W * (1.0 - hp["lr"] * hp["weight_decay"]) + step * self.A / d
+
+    def check(self, got, want, tol=1e-6):
+        """got/want: (w, m, v) triples.  Returns the worst error/scale ratio per array."""
+        out = {}
+        for name, a, b, scale in (("w", got[0], want[0], self.W), ("m", got[1], want[1], self.A),
+                                  ("v", got[2], want[2], np.abs(np.asarray(want[2], dtype=np.float64)))):
+            err = np.abs(np.asarray(a, dtype=np.float64) - np.asarray(b, dtype=np.float64))
+            bad = err > tol * scale
+            ratio = float(np.max(err / np.maximum(scale, 1e-300))) if err.size else 0.0
+            out[name] = ratio
+            assert not bad.any(), f"{name}: {int(bad.sum())} elements beyond {tol} x scale (worst {ratio:.3e})"
+        return out
+
+
+def ulp16_distance(a, b):
+    """Distance in units in the last place between two arrays of 16-bit sign-magnitude patterns."""
+    def order(x):
+        x = np.asarray(x, dtype=np.uint16).astype(np.int32)
+        return np.where(x & 0x8000, -(x & 0x7FFF), x & 0x7FFF)
+    return np.abs(order(a) - order(b))
