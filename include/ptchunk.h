@@ -1,0 +1,247 @@
+/* ptchunk — the chunk-based model-state hot path of ProTrain-style memory
+ * management, for one AMD MI355X (gfx950).
+ *
+ * Model states (16-bit parameters, 16-bit gradients, fp32 master weights, fp32
+ * momentum, fp32 variance: 16 bytes per parameter — paper, Introduction) are held
+ * in fixed-size flat CHUNKS (paper, "Hierarchical Chunk Management for Model
+ * States").  A prefix of the chunks is PERSISTENT: resident in GPU memory and
+ * updated there; the remaining chunks live in pinned host memory and pass through
+ * pre-allocated device chunk buffers when they are needed (same section; three
+ * buffers = prefetch / execute / offload, "Analysis of Searched Configurations").
+ * The parameter update is Adam in fp32 under mixed precision (Background;
+ * Appendix A.1, "Modeling Runtime").  The paper defines neither gradient clipping
+ * nor loss scaling nor the Adam variant; this library fixes them as: global
+ * L2-norm clipping with coefficient min(1, c/(norm+1e-6)); AdamW (decoupled decay,
+ * bias correction, eps added after the square root); dynamic loss scaling with
+ * skip-on-non-finite.
+ *
+ * One optimizer step is the call sequence
+ *     pt_chunk_pack_grads      gradients -> gradient chunks (+ per-chunk sum of squares, non-finite flag)
+ *     pt_chunk_grad_sqnorm     (optional recompute from chunks) + finalize: global norm, found_inf
+ *     pt_chunk_stream_step     host-resident chunks: H2D -> update -> D2H on side streams  (optional)
+ *     pt_chunk_adamw_step      GPU-resident chunks, one launch
+ *     pt_step_end              joins the side streams, advances the step counter / loss scale
+ * Everything is enqueued asynchronously; nothing in these five calls allocates or
+ * synchronises with the host (one exception, stated at pt_chunk_adamw_step).
+ *
+ * CONVENTIONS
+ *  - Plain C ABI.  Every function returns a pt_status (PT_OK == 0) and never
+ *    throws or aborts; pt_last_error(ctx) gives the text of the last failure.
+ *  - "device" pointers are HIP device addresses on the device that was current
+ *    at pt_ctx_create; "host" pointers are ordinary process memory; "pinned"
+ *    pointers are host memory from hipHostMalloc (or torch pin_memory).
+ *  - The CALLER owns all chunk memory (device and pinned) and the compute stream.
+ *    The library borrows pointers for the duration of the enqueued work.  The
+ *    context owns only its scratch (partials, device scalars, pointer tables),
+ *    its side streams and events, and the device chunk buffers of the streamed
+ *    path.
+ *  - Sizes and offsets are in ELEMENTS.  chunk_elems must be a multiple of 8.
+ *    Every chunk base pointer must be 16-byte aligned.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *  - A context is not thread-safe; use one per optimizer instance.
+ */
+#ifndef PTCHUNK_H
+#define PTCHUNK_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pt_ctx pt_ctx;
+typedef struct pt_pack_plan pt_pack_plan;
+
+typedef enum {
+  PT_OK = 0,
+  PT_ERR_INVALID_ARG = 1, /* NULL pointer, zero size, range outside the context's chunks ... */
+  PT_ERR_ALIGNMENT = 2,   /* chunk_elems not a multiple of 8, chunk base not 16-byte aligned */
+  PT_ERR_HIP = 3,         /* a HIP runtime call failed; text in pt_last_error */
+  PT_ERR_STATE = 4,       /* call out of order (update before the norm was finalized ...) */
+  PT_ERR_UNSUPPORTED = 5,
+  PT_ERR_NOMEM = 6
+} pt_status;
+
+typedef enum { PT_BF16 = 0, PT_FP16 = 1 } pt_dtype;
+
+/* One contiguous run of one tensor inside one chunk. */
+typedef struct {
+  const void* src;    /* device: first element of the tensor (16-bit elements)         */
+  uint64_t src_off;   /* first element of the run within the tensor                     */
+  uint64_t len;       /* elements in the run (> 0)                                      */
+  uint64_t chunk_off; /* first element of the run within the chunk                      */
+  uint32_t chunk;     /* destination chunk index                                        */
+  uint32_t tensor;    /* index of the tensor the run belongs to (filled by pt_layout_dense) */
+} pt_segment;
+
+/* Hyper-parameters of one update, in fp64 (the device derives its fp32 constants
+ * from these in fp64 and rounds once).  max_norm <= 0 disables clipping. */
+typedef struct {
+  double lr, beta1, beta2, eps, weight_decay, max_norm;
+} pt_hparams;
+
+/* Dynamic loss scaling.  Typical: init_scale 65536, growth 2, backoff 0.5,
+ * growth_interval 2000.  The scale never drops below 1. */
+typedef struct {
+  double init_scale, growth, backoff;
+  int32_t growth_interval;
+  int32_t reserved;
+} pt_scaler_cfg;
+
+/* Scalars of the step in flight (after finalize) or of the last step. */
+typedef struct {
+  double sqnorm;      /* sum over all chunks of (g / loss_scale)^2                     */
+  double norm;        /* sqrt(sqnorm)                                                    */
+  double clip_coef;   /* min(1, max_norm/(norm+1e-6)); valid once an update call ran     */
+  double loss_scale;  /* scale in force for this step                                    */
+  float grad_mult;    /* float(clip_coef / loss_scale): what the update kernel multiplies g by */
+  int32_t found_inf;  /* 1 if any gradient word is +-inf or NaN: the step is skipped     */
+  int32_t step;       /* number of APPLIED updates so far (not advanced by a skipped step) */
+  int32_t good_steps; /* consecutive finite steps since the last scale change            */
+} pt_step_report;
+
+/* The nine fp32 constants the update kernel used in the last update call:
+ * beta1, beta2, 1-beta1, 1-beta2, 1-lr*wd, lr/(1-beta1^t), 1/sqrt(1-beta2^t), eps, grad_mult. */
+typedef struct {
+  float c[9];
+  int32_t skip;
+} pt_update_consts;
+
+const char* pt_version(void);
+const char* pt_status_string(int status);
+/* Text of the last failure on this context ("" if none).  ctx may be NULL: then
+ * the text of the last failure of a call that had no context (pt_ctx_create). */
+const char* pt_last_error(const pt_ctx* ctx);
+
+/* ---- context ------------------------------------------------------------------
+ * Creates a context for n_chunks chunks of chunk_elems elements each, on the
+ * current HIP device.  Allocates the scratch (a few MB) and synchronises; not a hot
+ * call.  scaler == NULL: loss scale fixed at 1 (the bf16 configurations).
+ * A non-finite gradient skips the step in either case. */
+int pt_ctx_create(pt_ctx** out, int dtype, uint64_t chunk_elems, uint32_t n_chunks,
+                  const pt_scaler_cfg* scaler);
+int pt_ctx_destroy(pt_ctx* ctx);
+
+/* Overwrites the step counter / loss-scale state (resume).  Enqueued on stream. */
+int pt_ctx_set_state(pt_ctx* ctx, int32_t step, double loss_scale, int32_t good_steps, void* stream);
+
+/* ---- layout (host, integer only) ---------------------------------------------------
+ * Dense layout: the tensors are concatenated in the order given and cut every
+ * chunk_elems elements; a tensor may straddle a chunk boundary; only the tail of
+ * the last chunk is padding.  Writes up to `cap` segments (src = NULL, to be
+ * filled by the caller from `tensor`), the number of segments and of chunks.
+ * With out == NULL only the counts are computed.  Zero-sized tensors produce no
+ * segment. */
+int pt_layout_dense(const uint64_t* tensor_elems, uint32_t n_tensors, uint64_t chunk_elems,
+                    pt_segment* out, uint32_t cap, uint32_t* n_segments, uint32_t* n_chunks);
+
+/* ---- pack plan -----------------------------------------------------------------------
+ * Validates a segment table against the context (ranges inside chunks, no two
+ * segments overlapping in a chunk), cuts it into tiles and uploads the tile list.
+ * Allocates and synchronises: do it once, outside the step.  The plan records the
+ * src pointers; build a new plan when the gradient tensors move.
+ * segs: host array.  n_segs may be 0 (the plan then does nothing). */
+int pt_pack_plan_create(pt_ctx* ctx, const pt_segment* segs, uint32_t n_segs, pt_pack_plan** out);
+int pt_pack_plan_destroy(pt_pack_plan* plan);
+
+/* ---- the hot calls -------------------------------------------------------------------- */
+
+/* Gradients land in chunks (paper: gradients are one of the model states grouped
+ * into chunks; "Hierarchical Chunk Management for Model States").
+ * Copies every segment's 16-bit words, unchanged, into grad_chunks[seg.chunk] at
+ * chunk_off; fused with it, for every chunk the plan touches: the fp64 sum of
+ * (g/loss_scale)^2 over the segments' elements and a flag "some word is +-inf or
+ * NaN", left in the context for pt_chunk_grad_sqnorm(..., NULL, ...).
+ * Words of the chunk that no segment covers (padding) are not written.
+ * grad_chunks: host array of ctx.n_chunks device pointers (entries of chunks the
+ * plan does not touch may be NULL). */
+int pt_chunk_pack_grads(pt_ctx* ctx, const pt_pack_plan* plan, void* const* grad_chunks, void* stream);
+
+/* Inverse copy: chunk words -> the segments' tensors (e.g. updated 16-bit
+ * parameters back to the model's tensors; round-trip tests).  The segments' src
+ * pointers are written through. */
+int pt_chunk_unpack(pt_ctx* ctx, const pt_pack_plan* plan, const void* const* chunks, void* stream);
+
+/* Global gradient norm (not in the paper; the global L2 norm of the unscaled
+ * gradients, fp64 accumulation in a fixed order, bitwise reproducible run to run).
+ * grad_chunks != NULL: recomputes the per-chunk sum of squares and non-finite
+ *   flag of chunks [first_chunk, first_chunk+n_chunks) from the whole chunk
+ *   (padding is zero and adds nothing).  grad_chunks is a host array indexed by
+ *   absolute chunk number; only that range is read.
+ * grad_chunks == NULL: keeps the per-chunk values left by pt_chunk_pack_grads
+ *   (or by an earlier call: a chunk that was reduced on the GPU before it was
+ *   offloaded keeps its value).
+ * finalize != 0: sums the per-chunk values of ALL chunks of the context in chunk
+ *   order into sqnorm / norm / found_inf (device scalars) and opens the step for
+ *   the update calls. */
+int pt_chunk_grad_sqnorm(pt_ctx* ctx, const void* const* grad_chunks, uint32_t first_chunk,
+                         uint32_t n_chunks, int finalize, void* stream);
+
+/* Update of GPU-resident ("persistent") chunks (paper: persistent chunks reside
+ * on the GPU and are updated there; Appendix A.1 T_GPU_OPTIM).  For every element
+ * of chunks [first_chunk, first_chunk+n_chunks), padding included:
+ *     g  = decode(grad) * grad_mult                 grad_mult = clip_coef / loss_scale
+ *     m  = beta1 m + (1-beta1) g
+ *     v  = beta2 v + (1-beta2) g^2
+ *     w  = w (1 - lr wd) - lr/(1-beta1^t) * m / (sqrt(v)/sqrt(1-beta2^t) + eps)
+ *     param16 = round-to-nearest-even(w)
+ * in fp32 with correctly rounded operations, t = applied updates so far + 1.
+ * If the step's found_inf is set nothing is written.  One kernel launch covers
+ * all n_chunks chunks.
+ * grad/master/m/v/param16: host arrays of n_chunks device pointers (entry i is
+ * chunk first_chunk+i).  The context keeps a device copy of these tables; when a
+ * call presents pointers that differ from the copy, the table is re-uploaded
+ * after a hipStreamSynchronize(stream) — the only host synchronisation of a hot
+ * call, and it happens on the first call and whenever chunks move.
+ * Requires a finalized norm in this step (else PT_ERR_STATE). */
+int pt_chunk_adamw_step(pt_ctx* ctx, const pt_hparams* hp, uint32_t first_chunk, uint32_t n_chunks,
+                        const void* const* grad, float* const* master, float* const* m,
+                        float* const* v, void* const* param16, void* stream);
+
+/* Device chunk buffers for the streamed path (paper: pre-allocated chunk buffers
+ * for non-persistent chunks).  Allocates n_slots buffers of 16 bytes x chunk_elems,
+ * three side streams and the events.  n_slots >= 2.  Not a hot call. */
+int pt_stream_reserve(pt_ctx* ctx, uint32_t n_slots);
+
+/* Update of host-resident ("non-persistent") chunks through the chunk buffers
+ * (paper: non-persistent chunks are offloaded to CPU memory and moved over the
+ * CPU-GPU link, "Hierarchical Chunk Management for Model States"; upload/offload
+ * terms of Appendix A.1).  For chunk i of the range, slot = i mod n_slots:
+ *     upload stream : wait slot free; H2D grad(2B) + master, m, v (12B) per element
+ *     compute stream: wait upload;    the same update kernel on the slot
+ *     offload stream: wait kernel;    D2H master, m, v (12B) + param16 (2B); slot free
+ * so that uploads, kernels and offloads of neighbouring chunks overlap, and all
+ * of it overlaps whatever the caller enqueues on `stream` afterwards (typically
+ * pt_chunk_adamw_step for the resident chunks).  `stream` is only used to order
+ * the side streams after the work already enqueued on it (the finalized norm);
+ * pt_step_end(ctx, stream) joins them back.  Results are bit-identical to
+ * pt_chunk_adamw_step on the same data.  If the step is skipped the uploads and
+ * offloads still run: master, m and v come back unchanged and param16 comes back
+ * as round-to-nearest-even(master), which is what it held if it was produced by
+ * this library or initialised from the master weights.
+ * h_*: host arrays of n_chunks PINNED pointers (entry i is chunk first_chunk+i).
+ * Requires pt_stream_reserve and a finalized norm in this step. */
+int pt_chunk_stream_step(pt_ctx* ctx, const pt_hparams* hp, uint32_t first_chunk, uint32_t n_chunks,
+                         const void* const* h_grad, float* const* h_master, float* const* h_m,
+                         float* const* h_v, void* const* h_param16, void* stream);
+
+/* Closes the step: makes `stream` wait for the side streams of a streamed update,
+ * then on the device: found_inf ? (loss_scale = max(loss_scale*backoff, 1),
+ * good_steps = 0) : (step += 1, good_steps += 1, and loss_scale *= growth when
+ * good_steps reaches growth_interval).  Without a scaler only the counter moves. */
+int pt_step_end(pt_ctx* ctx, void* stream);
+
+/* ---- read-back (these synchronise `stream`) ----------------------------------------- */
+int pt_step_report_read(pt_ctx* ctx, pt_step_report* out, void* stream);
+int pt_update_consts_read(pt_ctx* ctx, pt_update_consts* out, void* stream);
+
+/* ---- test hook ------------------------------------------------------------------------
+ * Opens the step with the given scalars instead of a computed norm: the update
+ * kernel multiplies gradients by exactly `grad_mult` (no clipping on top) and
+ * skips if found_inf != 0.  For kernel-isolated tests. */
+int pt_step_override(pt_ctx* ctx, float grad_mult, int32_t found_inf, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PTCHUNK_H */

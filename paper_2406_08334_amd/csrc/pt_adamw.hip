@@ -1,0 +1,249 @@
+// Fused mixed-precision AdamW over chunks: one launch covers every chunk of a
+// range through the context's device pointer table.
+//
+// HBM-bound: per element 14 bytes read (g16, w, m, v) and 14 written (w, m, v,
+// p16).  Work unit = 4 consecutive elements per lane: one 16-byte access per fp32
+// array and one 8-byte access per 16-bit array, so that every wave instruction
+// touches one contiguous 1 KiB (fp32) or 512 B (16-bit) span.  UNROLL units per
+// lane are loaded before the first is used, to keep enough bytes in flight.
+// Arithmetic: the fp32 operation sequence below with correctly rounded *, fma,
+// sqrt and / (this file is compiled with contraction off and without fast-math).
+#include "pt_common.h"
+
+#include <hip/hip_fp16.h>
+
+#pragma clang fp contract(off)
+
+namespace {
+
+constexpr int AW_THREADS = 256;
+constexpr int AW_UNROLL = 4;
+constexpr uint32_t AW_TILE_UNITS = AW_THREADS * AW_UNROLL;  // 4-element units per tile (4096 elements)
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Derives the nine fp32 constants of this update from the fp64 hyper-parameters
+// and the step's device scalars (Adam bias correction with t = applied updates
+// + 1; clip coefficient min(1, c/(norm+1e-6)); unscale by the loss scale).
+__global__ void k_prepare(PtDevState* st, pt_hparams hp) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  const double t = double(st->step + 1);
+  double clip = 1.0;
+  float gm;
+  if (st->override_active) {
+    gm = st->override_grad_mult;
+  } else {
+    if (hp.max_norm > 0.0) {
+      double c = hp.max_norm / (st->norm + 1e-6);
+      clip = c < 1.0 ? c : 1.0;
+    }
+    gm = float(clip / st->loss_scale);
+  }
+  st->clip_coef = clip;
+  st->c[0] = float(hp.beta1);
+  st->c[1] = float(hp.beta2);
+  st->c[2] = float(1.0 - hp.beta1);
+  st->c[3] = float(1.0 - hp.beta2);
+  st->c[4] = float(1.0 - hp.lr * hp.weight_decay);
+  st->c[5] = float(hp.lr / (1.0 - pow(hp.beta1, t)));
+  st->c[6] = float(1.0 / sqrt(1.0 - pow(hp.beta2, t)));
+  st->c[7] = float(hp.eps);
+  st->c[8] = gm;
+  st->skip = st->found_inf ? 1 : 0;
+}
+
+template <int DT>
+__device__ __forceinline__ float decode16(uint32_t w16) {
+  if (DT == PT_BF16) {
+    return __uint_as_float(w16 << 16);
+  } else {
+    __half_raw r; r.x = (unsigned short)w16;
+    return __half2float(__half(r));
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ uint32_t encode16(float x) {
+  if (DT == PT_BF16) {
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x0040u;  // NaN stays NaN
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;                    // round to nearest, ties to even
+  } else {
+    __half_raw r = __half_raw(__float2half_rn(x));
+    return (uint32_t)r.x;
+  }
+}
+
+struct Consts { float b1, b2, omb1, omb2, decay, step_size, rsb2, eps, gm; };
+
+template <int DT>
+__device__ __forceinline__ void update_unit(const Consts& k, u32x2 g2, f32x4& w, f32x4& m, f32x4& v,
+                                            u32x2& p2) {
+  uint32_t gw[4] = {g2.x & 0xffffu, g2.x >> 16, g2.y & 0xffffu, g2.y >> 16};
+  uint32_t pw[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    // one correctly rounded binary32 operation per line; contraction is off for this file
+    float g = decode16<DT>(gw[j]) * k.gm;
+    float t1 = k.omb1 * g;
+    float mn = __builtin_fmaf(k.b1, m[j], t1);
+    float t2 = k.omb2 * g;
+    t2 = t2 * g;
+    float vn = __builtin_fmaf(k.b2, v[j], t2);
+    float d = __builtin_fmaf(__builtin_sqrtf(vn), k.rsb2, k.eps);
+    float u = mn / d;
+    float t3 = w[j] * k.decay;
+    float wn = __builtin_fmaf(-k.step_size, u, t3);
+    m[j] = mn; v[j] = vn; w[j] = wn;
+    pw[j] = encode16<DT>(wn);
+  }
+  p2.x = pw[0] | (pw[1] << 16);
+  p2.y = pw[2] | (pw[3] << 16);
+}
+
+// grid = (blocks_per_chunk, n_cols).  Block (bx, i) walks the tiles
+// bx, bx+gridDim.x, ... of the chunk in table column first_col+i.
+template <int DT>
+__global__ void __launch_bounds__(AW_THREADS)
+k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_col, uint64_t S,
+        const PtDevState* __restrict__ st, int recast_on_skip) {
+  if (st->skip) {
+    // Skipped step: nothing changes.  A chunk buffer of the streamed path is offloaded in
+    // full afterwards and its param16 array was never uploaded, so it is refilled from the
+    // untouched master weights (param16 == RNE(master) is the invariant of every update).
+    if (recast_on_skip) {
+      const f32x4* wq = reinterpret_cast<const f32x4*>(table[size_t(ROW_MASTER) * table_cols + first_col + blockIdx.y]);
+      u32x2* pq = reinterpret_cast<u32x2*>(table[size_t(ROW_P16) * table_cols + first_col + blockIdx.y]);
+      const uint64_t n_units = S / 4;
+      for (uint64_t u = uint64_t(blockIdx.x) * AW_THREADS + threadIdx.x; u < n_units;
+           u += uint64_t(gridDim.x) * AW_THREADS) {
+        f32x4 w = wq[u];
+        u32x2 p;
+        p.x = encode16<DT>(w[0]) | (encode16<DT>(w[1]) << 16);
+        p.y = encode16<DT>(w[2]) | (encode16<DT>(w[3]) << 16);
+        pq[u] = p;
+      }
+    }
+    return;
+  }
+  Consts k;
+  k.b1 = st->c[0]; k.b2 = st->c[1]; k.omb1 = st->c[2]; k.omb2 = st->c[3]; k.decay = st->c[4];
+  k.step_size = st->c[5]; k.rsb2 = st->c[6]; k.eps = st->c[7]; k.gm = st->c[8];
+
+  const uint32_t col = first_col + blockIdx.y;
+  const u32x2* __restrict__ gp = reinterpret_cast<const u32x2*>(table[size_t(ROW_GRAD) * table_cols + col]);
+  f32x4* __restrict__ wp = reinterpret_cast<f32x4*>(table[size_t(ROW_MASTER) * table_cols + col]);
+  f32x4* __restrict__ mp = reinterpret_cast<f32x4*>(table[size_t(ROW_M) * table_cols + col]);
+  f32x4* __restrict__ vp = reinterpret_cast<f32x4*>(table[size_t(ROW_V) * table_cols + col]);
+  u32x2* __restrict__ pp = reinterpret_cast<u32x2*>(table[size_t(ROW_P16) * table_cols + col]);
+
+  const uint64_t units = S / 4;
+  const uint64_t full_tiles = units / AW_TILE_UNITS;
+  for (uint64_t tile = blockIdx.x; tile < full_tiles; tile += gridDim.x) {
+    const uint64_t u0 = tile * AW_TILE_UNITS + threadIdx.x;
+    u32x2 g[AW_UNROLL]; f32x4 w[AW_UNROLL], m[AW_UNROLL], v[AW_UNROLL];
+#pragma unroll
+    for (int r = 0; r < AW_UNROLL; ++r) {
+      const uint64_t u = u0 + uint64_t(r) * AW_THREADS;
+      g[r] = __builtin_nontemporal_load(gp + u);
+      w[r] = __builtin_nontemporal_load(wp + u);
+      m[r] = __builtin_nontemporal_load(mp + u);
+      v[r] = __builtin_nontemporal_load(vp + u);
+    }
+#pragma unroll
+    for (int r = 0; r < AW_UNROLL; ++r) {
+      const uint64_t u = u0 + uint64_t(r) * AW_THREADS;
+      u32x2 p;
+      update_unit<DT>(k, g[r], w[r], m[r], v[r], p);
+      __builtin_nontemporal_store(w[r], wp + u);
+      __builtin_nontemporal_store(m[r], mp + u);
+      __builtin_nontemporal_store(v[r], vp + u);
+      __builtin_nontemporal_store(p, pp + u);
+    }
+  }
+  // ragged tail of the chunk (fewer than one tile of units), taken by block 0
+  if (blockIdx.x == 0) {
+    for (uint64_t u = full_tiles * AW_TILE_UNITS + threadIdx.x; u < units; u += AW_THREADS) {
+      u32x2 g = gp[u]; f32x4 w = wp[u], m = mp[u], v = vp[u]; u32x2 p;
+      update_unit<DT>(k, g, w, m, v, p);
+      wp[u] = w; mp[u] = m; vp[u] = v; pp[u] = p;
+    }
+  }
+}
+
+}  // namespace
+
+int pt_prepare_consts(pt_ctx* ctx, const pt_hparams* hp, hipStream_t stream) {
+  if (ctx->prepared) {
+    if (std::memcmp(&ctx->prepared_hp, hp, sizeof *hp) == 0) return PT_OK;
+    if (ctx->stream_pending)
+      return pt_fail(ctx, PT_ERR_STATE, "hyper-parameters changed while a streamed update of this step is in flight");
+  }
+  hipLaunchKernelGGL(k_prepare, dim3(1), dim3(1), 0, stream, ctx->d_state, *hp);
+  PT_LAUNCH_CHECK(ctx, "k_prepare");
+  ctx->prepared = true;
+  ctx->prepared_hp = *hp;
+  return PT_OK;
+}
+
+// Blocks per chunk: enough tiles per block to amortise the launch of a block,
+// enough blocks to fill 256 CUs many times over.
+static uint32_t adamw_blocks_per_chunk(const pt_ctx* ctx, uint32_t n_cols) {
+  uint64_t tiles = (ctx->S / 4) / AW_TILE_UNITS;
+  if (tiles == 0) return 1;
+  static int env_bpc = -1;
+  if (env_bpc < 0) {
+    const char* e = getenv("PTCHUNK_ADAMW_BLOCKS_PER_CHUNK");
+    env_bpc = e ? atoi(e) : 0;
+  }
+  uint64_t want;
+  if (env_bpc > 0) {
+    want = (uint64_t)env_bpc;
+  } else {
+    // aim at about 16 resident blocks per CU over the whole launch
+    uint64_t target_total = 256ull * 16ull;
+    want = (target_total + n_cols - 1) / n_cols;
+    if (want < 8) want = 8;
+  }
+  if (want > tiles) want = tiles;
+  if (want > 0x7fffffffull) want = 0x7fffffffull;
+  return (uint32_t)want;
+}
+
+int pt_launch_adamw(pt_ctx* ctx, uint32_t first_col, uint32_t n_cols, hipStream_t stream, bool recast_on_skip) {
+  if (n_cols == 0) return PT_OK;
+  dim3 grid(adamw_blocks_per_chunk(ctx, n_cols), n_cols);
+  if (ctx->dtype == PT_BF16)
+    hipLaunchKernelGGL(k_adamw<PT_BF16>, grid, dim3(AW_THREADS), 0, stream, ctx->d_table, ctx->table_cols,
+                       first_col, ctx->S, ctx->d_state, recast_on_skip ? 1 : 0);
+  else
+    hipLaunchKernelGGL(k_adamw<PT_FP16>, grid, dim3(AW_THREADS), 0, stream, ctx->d_table, ctx->table_cols,
+                       first_col, ctx->S, ctx->d_state, recast_on_skip ? 1 : 0);
+  PT_LAUNCH_CHECK(ctx, "k_adamw");
+  return PT_OK;
+}
+
+extern "C" int pt_chunk_adamw_step(pt_ctx* ctx, const pt_hparams* hp, uint32_t first_chunk, uint32_t n_chunks,
+                                   const void* const* grad, float* const* master, float* const* m,
+                                   float* const* v, void* const* param16, void* stream) {
+  if (!ctx) return PT_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  if (!hp) return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_chunk_adamw_step: hp is NULL");
+  if (uint64_t(first_chunk) + n_chunks > ctx->C)
+    return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_chunk_adamw_step: chunks [%u, %u) outside the context's %u chunks",
+                   first_chunk, first_chunk + n_chunks, ctx->C);
+  if (n_chunks && (!grad || !master || !m || !v || !param16))
+    return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_chunk_adamw_step: NULL pointer array");
+  if (!ctx->norm_finalized)
+    return pt_fail(ctx, PT_ERR_STATE, "pt_chunk_adamw_step: no finalized gradient norm in this step");
+  if (n_chunks == 0) return PT_OK;
+  int rc;
+  if ((rc = pt_table_bind(ctx, ROW_GRAD, first_chunk, n_chunks, grad, false, st, nullptr)) != PT_OK) return rc;
+  if ((rc = pt_table_bind(ctx, ROW_MASTER, first_chunk, n_chunks, (const void* const*)master, false, st, nullptr)) != PT_OK) return rc;
+  if ((rc = pt_table_bind(ctx, ROW_M, first_chunk, n_chunks, (const void* const*)m, false, st, nullptr)) != PT_OK) return rc;
+  if ((rc = pt_table_bind(ctx, ROW_V, first_chunk, n_chunks, (const void* const*)v, false, st, nullptr)) != PT_OK) return rc;
+  if ((rc = pt_table_bind(ctx, ROW_P16, first_chunk, n_chunks, (const void* const*)param16, false, st, nullptr)) != PT_OK) return rc;
+  if ((rc = pt_prepare_consts(ctx, hp, st)) != PT_OK) return rc;
+  return pt_launch_adamw(ctx, first_chunk, n_chunks, st, false);
+}

@@ -1,0 +1,151 @@
+// Internal declarations shared by the translation units of libptchunk.so.
+// Not part of the public boundary (that is include/ptchunk.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "ptchunk.h"
+
+// ---- device-resident scalars of a context ---------------------------------------
+// One instance per context, in device memory.  Written only by the single-thread
+// scalar kernels; read (uniformly) by the bulk kernels.
+struct PtDevState {
+  double sqnorm;
+  double norm;
+  double clip_coef;
+  double loss_scale;
+  double growth;
+  double backoff;
+  int32_t found_inf;
+  int32_t step;          // applied updates so far
+  int32_t good_steps;
+  int32_t growth_interval;
+  int32_t scaler_enabled;
+  int32_t override_active;
+  float override_grad_mult;
+  // constants of the update in flight (see pt_update_consts)
+  float c[9];
+  int32_t skip;
+};
+
+// Rows of the per-context device pointer table.  Each row has n_chunks + n_slots
+// entries; entries [n_chunks, n_chunks + n_slots) are the device chunk buffers
+// of the streamed path.
+enum PtRow : int {
+  ROW_GRAD = 0,
+  ROW_MASTER = 1,
+  ROW_M = 2,
+  ROW_V = 3,
+  ROW_P16 = 4,
+  ROW_PACK = 5,    // gradient chunks as seen by pack / sqnorm
+  ROW_UNPACK = 6,  // source chunks of unpack
+  N_ROWS = 7
+};
+
+constexpr uint32_t PT_MAX_SLOTS = 8;
+constexpr uint32_t PT_NORM_BLOCK_ELEMS = 32768;  // elements one block of the norm kernel reduces
+constexpr uint32_t PT_PACK_TILE_ELEMS = 16384;   // chunk-space tile of the pack kernel
+
+struct PtTile {        // one block of work of the pack / unpack kernels
+  uint64_t tensor_addr;  // byte address of the first element on the tensor side
+  uint64_t chunk_off;    // first element on the chunk side
+  uint32_t chunk;
+  uint32_t len;          // 1 .. PT_PACK_TILE_ELEMS
+};
+
+struct pt_pack_plan {
+  pt_ctx* ctx = nullptr;
+  uint32_t n_tiles = 0;
+  PtTile* d_tiles = nullptr;
+  uint32_t* d_chunk_tile_begin = nullptr;  // n_chunks + 1 entries (tiles sorted by chunk)
+  double* d_tile_sq = nullptr;
+  uint32_t* d_tile_flag = nullptr;
+  uint64_t total_elems = 0;
+  std::vector<uint32_t> touched;           // chunks that own at least one tile
+};
+
+struct pt_ctx {
+  int device = 0;
+  int dtype = PT_BF16;
+  uint64_t S = 0;          // chunk_elems
+  uint32_t C = 0;          // n_chunks
+  uint32_t norm_blocks = 0;  // blocks per chunk of the norm kernel
+  uint32_t table_cols = 0;   // C + PT_MAX_SLOTS
+  bool scaler = false;
+
+  PtDevState* d_state = nullptr;
+  uint64_t* d_table = nullptr;          // [N_ROWS][table_cols]
+  std::vector<uint64_t> h_table;        // host shadow of d_table
+  double* d_chunk_sq = nullptr;         // [C]
+  uint32_t* d_chunk_flag = nullptr;     // [C]
+  double* d_norm_part = nullptr;        // [C * norm_blocks]
+  uint32_t* d_norm_flag = nullptr;      // [C * norm_blocks]
+
+  // host-side step bookkeeping
+  bool norm_finalized = false;
+  bool prepared = false;
+  pt_hparams prepared_hp{};
+
+  // streamed path
+  uint32_t n_slots = 0;
+  void* slot_mem[PT_MAX_SLOTS] = {};
+  hipStream_t s_up = nullptr, s_comp = nullptr, s_down = nullptr;
+  hipEvent_t ev_fork = nullptr;
+  hipEvent_t ev_up[PT_MAX_SLOTS] = {}, ev_k[PT_MAX_SLOTS] = {}, ev_down[PT_MAX_SLOTS] = {};
+  bool slot_used[PT_MAX_SLOTS] = {};
+  bool stream_pending = false;
+  uint32_t last_slot = 0;
+
+  std::string err;
+};
+
+// ---- error plumbing ----------------------------------------------------------------
+int pt_fail(pt_ctx* ctx, int status, const char* fmt, ...);
+
+#define PT_HIP(ctx, call)                                                              \
+  do {                                                                                 \
+    hipError_t e__ = (call);                                                           \
+    if (e__ != hipSuccess)                                                             \
+      return pt_fail((ctx), PT_ERR_HIP, "%s failed: %s (%s:%d)", #call,                \
+                     hipGetErrorString(e__), __FILE__, __LINE__);                      \
+  } while (0)
+
+#define PT_LAUNCH_CHECK(ctx, name)                                                     \
+  do {                                                                                 \
+    hipError_t e__ = hipGetLastError();                                                \
+    if (e__ != hipSuccess)                                                             \
+      return pt_fail((ctx), PT_ERR_HIP, "launch of %s failed: %s", (name),             \
+                     hipGetErrorString(e__));                                          \
+  } while (0)
+
+// ---- helpers implemented in pt_ctx.hip ---------------------------------------------
+// Makes rows[r][first .. first+n) of the device pointer table equal to ptrs[0..n);
+// re-uploads (after synchronising `stream`) only when something changed.
+// allow_null: NULL entries are accepted (and stored as 0).
+int pt_table_bind(pt_ctx* ctx, int row, uint32_t first, uint32_t n, const void* const* ptrs,
+                  bool allow_null, hipStream_t stream, bool* changed);
+inline const uint64_t* pt_row(const pt_ctx* ctx, int row) {
+  return ctx->d_table + size_t(row) * ctx->table_cols;
+}
+
+// ---- implemented in pt_adamw.hip ------------------------------------------------------
+// Runs the scalar "prepare" kernel if this step's constants are not yet derived
+// from `hp`, then launches the update kernel over table columns
+// [first_col, first_col + n_cols).
+int pt_prepare_consts(pt_ctx* ctx, const pt_hparams* hp, hipStream_t stream);
+// recast_on_skip: on a skipped step rewrite param16 = RNE(master) instead of doing nothing.
+int pt_launch_adamw(pt_ctx* ctx, uint32_t first_col, uint32_t n_cols, hipStream_t stream, bool recast_on_skip);
+
+// ---- implemented in pt_norm.hip ---------------------------------------------------------
+// Sums per-block partials into per-chunk values.  uniform mode (tile_begin == NULL):
+// chunk first+i owns partials [i*per_chunk, (i+1)*per_chunk).
+int pt_launch_chunk_reduce(pt_ctx* ctx, const double* part, const uint32_t* flag,
+                           const uint32_t* tile_begin, uint32_t first, uint32_t n,
+                           uint32_t per_chunk, hipStream_t stream);

@@ -1,0 +1,288 @@
+// Context, error plumbing, pointer tables, host-side layout builder and the
+// single-thread scalar kernels (state set / override / step end).
+#include "pt_common.h"
+
+static thread_local std::string g_noctx_error;
+
+int pt_fail(pt_ctx* ctx, int status, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (ctx) ctx->err = buf; else g_noctx_error = buf;
+  return status;
+}
+
+// ---- scalar kernels ------------------------------------------------------------------
+
+__global__ void k_init_state(PtDevState* st, double loss_scale, double growth, double backoff,
+                             int32_t growth_interval, int32_t scaler_enabled) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  st->sqnorm = 0.0; st->norm = 0.0; st->clip_coef = 1.0;
+  st->loss_scale = loss_scale; st->growth = growth; st->backoff = backoff;
+  st->found_inf = 0; st->step = 0; st->good_steps = 0;
+  st->growth_interval = growth_interval; st->scaler_enabled = scaler_enabled;
+  st->override_active = 0; st->override_grad_mult = 1.0f;
+  for (int i = 0; i < 9; ++i) st->c[i] = 0.0f;
+  st->skip = 0;
+}
+
+__global__ void k_set_state(PtDevState* st, int32_t step, double loss_scale, int32_t good_steps) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  st->step = step; st->loss_scale = loss_scale; st->good_steps = good_steps;
+}
+
+__global__ void k_override(PtDevState* st, float grad_mult, int32_t found_inf) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  st->override_active = 1; st->override_grad_mult = grad_mult; st->found_inf = found_inf;
+  st->sqnorm = 0.0; st->norm = 0.0;
+}
+
+// Loss-scale machine and step counter (dynamic loss scaling with skip on
+// non-finite gradients; the counter does not move on a skipped step).
+__global__ void k_step_end(PtDevState* st) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  if (st->found_inf) {
+    if (st->scaler_enabled) {
+      double s = st->loss_scale * st->backoff;
+      st->loss_scale = s > 1.0 ? s : 1.0;
+      st->good_steps = 0;
+    }
+  } else {
+    st->step += 1;
+    if (st->scaler_enabled) {
+      st->good_steps += 1;
+      if (st->good_steps >= st->growth_interval) {
+        st->loss_scale = st->loss_scale * st->growth;
+        st->good_steps = 0;
+      }
+    }
+  }
+  st->override_active = 0;
+}
+
+// ---- public: misc -------------------------------------------------------------------------
+
+extern "C" const char* pt_version(void) { return "ptchunk 0.1 (gfx950)"; }
+
+extern "C" const char* pt_status_string(int s) {
+  switch (s) {
+    case PT_OK: return "PT_OK";
+    case PT_ERR_INVALID_ARG: return "PT_ERR_INVALID_ARG";
+    case PT_ERR_ALIGNMENT: return "PT_ERR_ALIGNMENT";
+    case PT_ERR_HIP: return "PT_ERR_HIP";
+    case PT_ERR_STATE: return "PT_ERR_STATE";
+    case PT_ERR_UNSUPPORTED: return "PT_ERR_UNSUPPORTED";
+    case PT_ERR_NOMEM: return "PT_ERR_NOMEM";
+    default: return "PT_ERR_UNKNOWN";
+  }
+}
+
+extern "C" const char* pt_last_error(const pt_ctx* ctx) {
+  return ctx ? ctx->err.c_str() : g_noctx_error.c_str();
+}
+
+// ---- public: context ----------------------------------------------------------------------
+
+static void ctx_free_all(pt_ctx* ctx) {
+  if (ctx->s_up) (void)hipStreamDestroy(ctx->s_up);
+  if (ctx->s_comp) (void)hipStreamDestroy(ctx->s_comp);
+  if (ctx->s_down) (void)hipStreamDestroy(ctx->s_down);
+  if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+  for (uint32_t s = 0; s < PT_MAX_SLOTS; ++s) {
+    if (ctx->ev_up[s]) (void)hipEventDestroy(ctx->ev_up[s]);
+    if (ctx->ev_k[s]) (void)hipEventDestroy(ctx->ev_k[s]);
+    if (ctx->ev_down[s]) (void)hipEventDestroy(ctx->ev_down[s]);
+    if (ctx->slot_mem[s]) (void)hipFree(ctx->slot_mem[s]);
+  }
+  if (ctx->d_state) (void)hipFree(ctx->d_state);
+  if (ctx->d_table) (void)hipFree(ctx->d_table);
+  if (ctx->d_chunk_sq) (void)hipFree(ctx->d_chunk_sq);
+  if (ctx->d_chunk_flag) (void)hipFree(ctx->d_chunk_flag);
+  if (ctx->d_norm_part) (void)hipFree(ctx->d_norm_part);
+  if (ctx->d_norm_flag) (void)hipFree(ctx->d_norm_flag);
+}
+
+static int ctx_alloc(pt_ctx* ctx, const pt_scaler_cfg* sc) {
+  PT_HIP(ctx, hipGetDevice(&ctx->device));
+  PT_HIP(ctx, hipMalloc(&ctx->d_state, sizeof(PtDevState)));
+  size_t tab_bytes = size_t(N_ROWS) * ctx->table_cols * sizeof(uint64_t);
+  PT_HIP(ctx, hipMalloc(&ctx->d_table, tab_bytes));
+  PT_HIP(ctx, hipMemset(ctx->d_table, 0, tab_bytes));
+  ctx->h_table.assign(size_t(N_ROWS) * ctx->table_cols, 0);
+  PT_HIP(ctx, hipMalloc(&ctx->d_chunk_sq, ctx->C * sizeof(double)));
+  PT_HIP(ctx, hipMemset(ctx->d_chunk_sq, 0, ctx->C * sizeof(double)));
+  PT_HIP(ctx, hipMalloc(&ctx->d_chunk_flag, ctx->C * sizeof(uint32_t)));
+  PT_HIP(ctx, hipMemset(ctx->d_chunk_flag, 0, ctx->C * sizeof(uint32_t)));
+  size_t np = size_t(ctx->C) * ctx->norm_blocks;
+  PT_HIP(ctx, hipMalloc(&ctx->d_norm_part, np * sizeof(double)));
+  PT_HIP(ctx, hipMalloc(&ctx->d_norm_flag, np * sizeof(uint32_t)));
+  double init = sc ? sc->init_scale : 1.0;
+  hipLaunchKernelGGL(k_init_state, dim3(1), dim3(1), 0, nullptr, ctx->d_state, init,
+                     sc ? sc->growth : 1.0, sc ? sc->backoff : 1.0,
+                     sc ? sc->growth_interval : 0, sc ? 1 : 0);
+  PT_LAUNCH_CHECK(ctx, "k_init_state");
+  PT_HIP(ctx, hipDeviceSynchronize());
+  return PT_OK;
+}
+
+extern "C" int pt_ctx_create(pt_ctx** out, int dtype, uint64_t chunk_elems, uint32_t n_chunks,
+                             const pt_scaler_cfg* scaler) {
+  if (!out) return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_ctx_create: out is NULL");
+  *out = nullptr;
+  if (dtype != PT_BF16 && dtype != PT_FP16)
+    return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_ctx_create: dtype %d is neither PT_BF16 nor PT_FP16", dtype);
+  if (chunk_elems == 0 || n_chunks == 0)
+    return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_ctx_create: chunk_elems and n_chunks must be > 0");
+  if (chunk_elems % 8 != 0)
+    return pt_fail(nullptr, PT_ERR_ALIGNMENT, "pt_ctx_create: chunk_elems %llu is not a multiple of 8",
+                   (unsigned long long)chunk_elems);
+  if (chunk_elems > (uint64_t(1) << 40) || n_chunks > 60000)
+    return pt_fail(nullptr, PT_ERR_UNSUPPORTED, "pt_ctx_create: chunk_elems > 2^40 or n_chunks > 60000");
+  if (scaler) {
+    if (!(scaler->init_scale >= 1.0) || !(scaler->growth >= 1.0) || !(scaler->backoff > 0.0) ||
+        !(scaler->backoff <= 1.0) || scaler->growth_interval < 1)
+      return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_ctx_create: scaler needs init_scale >= 1, growth >= 1, "
+                     "0 < backoff <= 1, growth_interval >= 1");
+  }
+  pt_ctx* ctx = new (std::nothrow) pt_ctx();
+  if (!ctx) return pt_fail(nullptr, PT_ERR_NOMEM, "pt_ctx_create: out of host memory");
+  ctx->dtype = dtype;
+  ctx->S = chunk_elems;
+  ctx->C = n_chunks;
+  ctx->norm_blocks = uint32_t((chunk_elems + PT_NORM_BLOCK_ELEMS - 1) / PT_NORM_BLOCK_ELEMS);
+  ctx->table_cols = n_chunks + PT_MAX_SLOTS;
+  ctx->scaler = scaler != nullptr;
+  int rc = ctx_alloc(ctx, scaler);
+  if (rc != PT_OK) {
+    g_noctx_error = ctx->err;
+    ctx_free_all(ctx);
+    delete ctx;
+    return rc;
+  }
+  *out = ctx;
+  return PT_OK;
+}
+
+extern "C" int pt_ctx_destroy(pt_ctx* ctx) {
+  if (!ctx) return PT_OK;
+  (void)hipDeviceSynchronize();
+  ctx_free_all(ctx);
+  delete ctx;
+  return PT_OK;
+}
+
+extern "C" int pt_ctx_set_state(pt_ctx* ctx, int32_t step, double loss_scale, int32_t good_steps,
+                                void* stream) {
+  if (!ctx) return PT_ERR_INVALID_ARG;
+  if (step < 0 || good_steps < 0 || !(loss_scale >= 1.0))
+    return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_ctx_set_state: step, good_steps >= 0 and loss_scale >= 1 required");
+  if (!ctx->scaler && loss_scale != 1.0)
+    return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_ctx_set_state: context has no scaler, loss_scale must be 1");
+  hipLaunchKernelGGL(k_set_state, dim3(1), dim3(1), 0, (hipStream_t)stream, ctx->d_state, step,
+                     loss_scale, good_steps);
+  PT_LAUNCH_CHECK(ctx, "k_set_state");
+  return PT_OK;
+}
+
+extern "C" int pt_step_override(pt_ctx* ctx, float grad_mult, int32_t found_inf, void* stream) {
+  if (!ctx) return PT_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(k_override, dim3(1), dim3(1), 0, (hipStream_t)stream, ctx->d_state, grad_mult,
+                     found_inf ? 1 : 0);
+  PT_LAUNCH_CHECK(ctx, "k_override");
+  ctx->norm_finalized = true;
+  ctx->prepared = false;
+  return PT_OK;
+}
+
+extern "C" int pt_step_end(pt_ctx* ctx, void* stream) {
+  if (!ctx) return PT_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  if (ctx->stream_pending) {
+    // offloads complete in order on one stream: the last one recorded covers them all
+    PT_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_down[ctx->last_slot], 0));
+    ctx->stream_pending = false;
+  }
+  hipLaunchKernelGGL(k_step_end, dim3(1), dim3(1), 0, st, ctx->d_state);
+  PT_LAUNCH_CHECK(ctx, "k_step_end");
+  ctx->norm_finalized = false;
+  ctx->prepared = false;
+  return PT_OK;
+}
+
+extern "C" int pt_step_report_read(pt_ctx* ctx, pt_step_report* out, void* stream) {
+  if (!ctx || !out) return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_step_report_read: NULL argument");
+  PtDevState h;
+  PT_HIP(ctx, hipMemcpyAsync(&h, ctx->d_state, sizeof h, hipMemcpyDeviceToHost, (hipStream_t)stream));
+  PT_HIP(ctx, hipStreamSynchronize((hipStream_t)stream));
+  out->sqnorm = h.sqnorm; out->norm = h.norm; out->clip_coef = h.clip_coef;
+  out->loss_scale = h.loss_scale; out->grad_mult = h.c[8]; out->found_inf = h.found_inf;
+  out->step = h.step; out->good_steps = h.good_steps;
+  return PT_OK;
+}
+
+extern "C" int pt_update_consts_read(pt_ctx* ctx, pt_update_consts* out, void* stream) {
+  if (!ctx || !out) return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_update_consts_read: NULL argument");
+  PtDevState h;
+  PT_HIP(ctx, hipMemcpyAsync(&h, ctx->d_state, sizeof h, hipMemcpyDeviceToHost, (hipStream_t)stream));
+  PT_HIP(ctx, hipStreamSynchronize((hipStream_t)stream));
+  for (int i = 0; i < 9; ++i) out->c[i] = h.c[i];
+  out->skip = h.skip;
+  return PT_OK;
+}
+
+// ---- pointer table -------------------------------------------------------------------------
+
+int pt_table_bind(pt_ctx* ctx, int row, uint32_t first, uint32_t n, const void* const* ptrs,
+                  bool allow_null, hipStream_t stream, bool* changed) {
+  uint64_t* h = ctx->h_table.data() + size_t(row) * ctx->table_cols + first;
+  bool diff = false;
+  for (uint32_t i = 0; i < n; ++i) {
+    uint64_t p = (uint64_t)(uintptr_t)ptrs[i];
+    if (!p && !allow_null) return pt_fail(ctx, PT_ERR_INVALID_ARG, "chunk pointer %u of row %d is NULL", first + i, row);
+    if (p & 15) return pt_fail(ctx, PT_ERR_ALIGNMENT, "chunk pointer %u of row %d is not 16-byte aligned", first + i, row);
+    if (h[i] != p) diff = true;
+  }
+  if (diff) {
+    for (uint32_t i = 0; i < n; ++i) h[i] = (uint64_t)(uintptr_t)ptrs[i];
+    // Work already enqueued may still read the old entries: drain it first.
+    PT_HIP(ctx, hipStreamSynchronize(stream));
+    PT_HIP(ctx, hipMemcpy(ctx->d_table + size_t(row) * ctx->table_cols + first, h, n * sizeof(uint64_t),
+                          hipMemcpyHostToDevice));
+  }
+  if (changed) *changed = diff;
+  return PT_OK;
+}
+
+// ---- layout -----------------------------------------------------------------------------------
+
+extern "C" int pt_layout_dense(const uint64_t* tensor_elems, uint32_t n_tensors, uint64_t chunk_elems,
+                               pt_segment* out, uint32_t cap, uint32_t* n_segments, uint32_t* n_chunks) {
+  if ((!tensor_elems && n_tensors) || !n_segments || !n_chunks)
+    return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_layout_dense: NULL argument");
+  if (chunk_elems == 0) return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_layout_dense: chunk_elems is 0");
+  if (chunk_elems % 8 != 0)
+    return pt_fail(nullptr, PT_ERR_ALIGNMENT, "pt_layout_dense: chunk_elems is not a multiple of 8");
+  uint64_t pos = 0;       // global element offset
+  uint64_t nseg = 0;
+  for (uint32_t t = 0; t < n_tensors; ++t) {
+    uint64_t left = tensor_elems[t], off = 0;
+    if (pos + left < pos) return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_layout_dense: total size overflows");
+    while (left) {
+      uint64_t c = pos / chunk_elems, in = pos % chunk_elems;
+      uint64_t run = chunk_elems - in < left ? chunk_elems - in : left;
+      if (c > 0xfffffffeull) return pt_fail(nullptr, PT_ERR_UNSUPPORTED, "pt_layout_dense: too many chunks");
+      if (out) {
+        if (nseg >= cap) return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_layout_dense: cap %u too small", cap);
+        pt_segment& s = out[nseg];
+        s.src = nullptr; s.src_off = off; s.len = run; s.chunk_off = in; s.chunk = uint32_t(c); s.tensor = t;
+      }
+      ++nseg; pos += run; off += run; left -= run;
+    }
+  }
+  if (nseg > 0xffffffffull) return pt_fail(nullptr, PT_ERR_UNSUPPORTED, "pt_layout_dense: too many segments");
+  *n_segments = uint32_t(nseg);
+  *n_chunks = uint32_t((pos + chunk_elems - 1) / chunk_elems);
+  return PT_OK;
+}

@@ -1,0 +1,191 @@
+// Global gradient norm: per-block fp64 partial sums of squares over gradient
+// chunks, a fixed-order per-chunk reduction, and the finalize step.
+//
+// HBM-bound: 2 bytes read per element.  Each lane issues 16-byte loads that are
+// contiguous across the wavefront (1 KiB per wave instruction), converts every
+// 16-bit word to fp64 and accumulates squares in fp64 (two 16-bit significands
+// multiply exactly, so only the additions round).  Reduction order is fixed:
+// lane-serial, then a 64-lane shuffle tree, then the four waves through LDS, then
+// one slot per block - no atomics, so results are bitwise reproducible.
+#include "pt_common.h"
+
+#include <hip/hip_fp16.h>
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int NB_THREADS = 256;
+
+template <int DT>
+__device__ __forceinline__ double word_to_f64(uint32_t w16) {
+  if (DT == PT_BF16) {
+    return (double)__uint_as_float(w16 << 16);
+  } else {
+    __half_raw r; r.x = (unsigned short)w16;
+    return (double)__half2float(__half(r));
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ uint32_t pair_nonfinite(uint32_t two_words) {
+  // exponent field all ones in either half
+  constexpr uint32_t E = DT == PT_BF16 ? 0x7f80u : 0x7c00u;
+  uint32_t lo = two_words & E, hi = (two_words >> 16) & E;
+  return (lo == E) | (hi == E);
+}
+
+template <int DT>
+__device__ __forceinline__ void accum_vec(const u32x4& q, double inv_scale, double& a0, double& a1,
+                                          uint32_t& flag) {
+  const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    double x0 = word_to_f64<DT>(w[k] & 0xffffu) * inv_scale;
+    double x1 = word_to_f64<DT>(w[k] >> 16) * inv_scale;
+    a0 = fma(x0, x0, a0);
+    a1 = fma(x1, x1, a1);
+    flag |= pair_nonfinite<DT>(w[k]);
+  }
+}
+
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x += __shfl_down(x, off, 64);
+  return x;  // valid in lane 0
+}
+
+// Block-wide sum in a fixed order; result valid in thread 0.
+__device__ __forceinline__ void block_sum(double& acc, uint32_t& flag) {
+  __shared__ double s_sum[NB_THREADS / 64];
+  __shared__ uint32_t s_flag[NB_THREADS / 64];
+  double w = wave_sum(acc);
+  uint32_t f = __any(flag != 0) ? 1u : 0u;
+  int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+  if (lane == 0) { s_sum[wid] = w; s_flag[wid] = f; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = s_sum[0];
+    uint32_t g = s_flag[0];
+#pragma unroll
+    for (int i = 1; i < NB_THREADS / 64; ++i) { t += s_sum[i]; g |= s_flag[i]; }
+    acc = t; flag = g;
+  }
+}
+
+// grid = (norm_blocks, n_chunks).  Block (b, i) reduces elements
+// [b*PT_NORM_BLOCK_ELEMS, min(S, (b+1)*PT_NORM_BLOCK_ELEMS)) of chunk first+i.
+template <int DT>
+__global__ void __launch_bounds__(NB_THREADS)
+k_sqnorm(const uint64_t* __restrict__ grad_row, uint32_t first, uint64_t S,
+         const PtDevState* __restrict__ st, double* __restrict__ part, uint32_t* __restrict__ flagout) {
+  const uint32_t b = blockIdx.x, i = blockIdx.y;
+  const u32x4* base = reinterpret_cast<const u32x4*>(grad_row[first + i]);
+  const uint64_t vec_total = S / 8;
+  const uint64_t v0 = uint64_t(b) * (PT_NORM_BLOCK_ELEMS / 8);
+  uint64_t v1 = v0 + PT_NORM_BLOCK_ELEMS / 8;
+  if (v1 > vec_total) v1 = vec_total;
+  const double inv_scale = 1.0 / st->loss_scale;
+  double a0 = 0.0, a1 = 0.0;
+  uint32_t flag = 0;
+  uint64_t v = v0 + threadIdx.x;
+  // four independent 16-byte loads in flight per lane
+  for (; v + 3 * NB_THREADS < v1; v += 4 * NB_THREADS) {
+    u32x4 q0 = __builtin_nontemporal_load(base + v);
+    u32x4 q1 = __builtin_nontemporal_load(base + v + NB_THREADS);
+    u32x4 q2 = __builtin_nontemporal_load(base + v + 2 * NB_THREADS);
+    u32x4 q3 = __builtin_nontemporal_load(base + v + 3 * NB_THREADS);
+    accum_vec<DT>(q0, inv_scale, a0, a1, flag);
+    accum_vec<DT>(q1, inv_scale, a0, a1, flag);
+    accum_vec<DT>(q2, inv_scale, a0, a1, flag);
+    accum_vec<DT>(q3, inv_scale, a0, a1, flag);
+  }
+  for (; v < v1; v += NB_THREADS) {
+    u32x4 q = __builtin_nontemporal_load(base + v);
+    accum_vec<DT>(q, inv_scale, a0, a1, flag);
+  }
+  double acc = a0 + a1;
+  block_sum(acc, flag);
+  if (threadIdx.x == 0) {
+    size_t slot = size_t(i) * gridDim.x + b;
+    part[slot] = acc;
+    flagout[slot] = flag;
+  }
+}
+
+// One block per chunk: sums that chunk's partials (lane-strided serial sums, then
+// the fixed block tree).  tile_begin == NULL: chunk first+i owns
+// [i*per_chunk, (i+1)*per_chunk); otherwise [tile_begin[c], tile_begin[c+1]) and a
+// chunk with an empty range keeps its previous value.
+__global__ void __launch_bounds__(NB_THREADS)
+k_chunk_reduce(const double* __restrict__ part, const uint32_t* __restrict__ flag,
+               const uint32_t* __restrict__ tile_begin, uint32_t first, uint32_t per_chunk,
+               double* __restrict__ chunk_sq, uint32_t* __restrict__ chunk_flag) {
+  const uint32_t i = blockIdx.x, c = first + i;
+  uint32_t lo, hi;
+  if (tile_begin) { lo = tile_begin[c]; hi = tile_begin[c + 1]; if (lo == hi) return; }
+  else { lo = i * per_chunk; hi = lo + per_chunk; }
+  double acc = 0.0;
+  uint32_t f = 0;
+  for (uint32_t k = lo + threadIdx.x; k < hi; k += NB_THREADS) { acc += part[k]; f |= flag[k]; }
+  block_sum(acc, f);
+  if (threadIdx.x == 0) { chunk_sq[c] = acc; chunk_flag[c] = f; }
+}
+
+// Sums the per-chunk values of all chunks in chunk order (single thread: C is a
+// few hundred at most) and publishes the step's scalars.
+__global__ void k_finalize(const double* __restrict__ chunk_sq, const uint32_t* __restrict__ chunk_flag,
+                           uint32_t C, PtDevState* st) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  double t = 0.0;
+  uint32_t f = 0;
+  for (uint32_t c = 0; c < C; ++c) { t += chunk_sq[c]; f |= chunk_flag[c]; }
+  st->sqnorm = t;
+  st->norm = sqrt(t);
+  st->found_inf = f ? 1 : 0;
+  st->override_active = 0;
+}
+
+}  // namespace
+
+int pt_launch_chunk_reduce(pt_ctx* ctx, const double* part, const uint32_t* flag,
+                           const uint32_t* tile_begin, uint32_t first, uint32_t n,
+                           uint32_t per_chunk, hipStream_t stream) {
+  if (n == 0) return PT_OK;
+  hipLaunchKernelGGL(k_chunk_reduce, dim3(n), dim3(NB_THREADS), 0, stream, part, flag, tile_begin,
+                     first, per_chunk, ctx->d_chunk_sq, ctx->d_chunk_flag);
+  PT_LAUNCH_CHECK(ctx, "k_chunk_reduce");
+  return PT_OK;
+}
+
+extern "C" int pt_chunk_grad_sqnorm(pt_ctx* ctx, const void* const* grad_chunks, uint32_t first_chunk,
+                                    uint32_t n_chunks, int finalize, void* stream) {
+  if (!ctx) return PT_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  if (uint64_t(first_chunk) + n_chunks > ctx->C)
+    return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_chunk_grad_sqnorm: chunks [%u, %u) outside the context's %u chunks",
+                   first_chunk, first_chunk + n_chunks, ctx->C);
+  if (grad_chunks && n_chunks) {
+    int rc = pt_table_bind(ctx, ROW_PACK, first_chunk, n_chunks, grad_chunks + first_chunk, false, st, nullptr);
+    if (rc != PT_OK) return rc;
+    dim3 grid(ctx->norm_blocks, n_chunks);
+    if (ctx->dtype == PT_BF16)
+      hipLaunchKernelGGL(k_sqnorm<PT_BF16>, grid, dim3(NB_THREADS), 0, st, pt_row(ctx, ROW_PACK), first_chunk,
+                         ctx->S, ctx->d_state, ctx->d_norm_part, ctx->d_norm_flag);
+    else
+      hipLaunchKernelGGL(k_sqnorm<PT_FP16>, grid, dim3(NB_THREADS), 0, st, pt_row(ctx, ROW_PACK), first_chunk,
+                         ctx->S, ctx->d_state, ctx->d_norm_part, ctx->d_norm_flag);
+    PT_LAUNCH_CHECK(ctx, "k_sqnorm");
+    int rc2 = pt_launch_chunk_reduce(ctx, ctx->d_norm_part, ctx->d_norm_flag, nullptr, first_chunk, n_chunks,
+                                     ctx->norm_blocks, st);
+    if (rc2 != PT_OK) return rc2;
+  }
+  if (finalize) {
+    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(64), 0, st, ctx->d_chunk_sq, ctx->d_chunk_flag, ctx->C,
+                       ctx->d_state);
+    PT_LAUNCH_CHECK(ctx, "k_finalize");
+    ctx->norm_finalized = true;
+    ctx->prepared = false;
+  }
+  return PT_OK;
+}

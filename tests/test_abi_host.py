@@ -1,0 +1,97 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol the header declares, the integer layout builder agrees with the oracle's
+index map, and argument validation returns error codes instead of crashing."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2406_08334_amd import binding as B
+from paper_2406_08334_amd import shapes
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "ptchunk.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pt_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    names = declared_functions()
+    assert len(names) >= 19
+    for n in names:
+        assert hasattr(L, n), f"{n} is declared in ptchunk.h but not exported"
+    assert sorted(B.EXPORTS) == names            # the binding covers the whole header
+    assert "ptchunk" in B.pt_version()
+    assert B.status_string(0) == "PT_OK" and B.status_string(4) == "PT_ERR_STATE"
+
+
+def test_layout_dense_matches_the_oracle_index_map(orc):
+    rng = np.random.default_rng(2)
+    for S, sizes in ((8, [1, 3, 7, 8, 9, 17]), (16, [16, 16, 1, 0, 40]), (64, [5, 300, 2, 64, 1])):
+        segs, n_chunks = B.pt_layout_dense(sizes, S)
+        tensors = [rng.integers(0, 1 << 16, size=n, dtype=np.uint16) for n in sizes]
+        want = orc.pack_dense(tensors, S)
+        assert n_chunks == want.shape[0]
+        got = np.zeros_like(want)
+        cover = np.zeros(want.shape, dtype=np.int32)
+        for s in segs:
+            assert s.len > 0 and s.chunk_off + s.len <= S and s.chunk < n_chunks
+            got[s.chunk, s.chunk_off:s.chunk_off + s.len] = tensors[s.tensor][s.src_off:s.src_off + s.len]
+            cover[s.chunk, s.chunk_off:s.chunk_off + s.len] += 1
+        assert np.array_equal(got, want)
+        assert cover.reshape(-1)[:sum(sizes)].min() == 1 and cover.max() == 1      # a partition
+        assert cover.reshape(-1)[sum(sizes):].sum() == 0                           # padding untouched
+
+
+def test_layout_dense_gpt2_block_worked_example():
+    table, S = shapes.workload("gpt2_block_768")
+    segs, n_chunks = B.pt_layout_dense([n for _, n in table], S)
+    assert n_chunks == 2 and len(segs) == 13                  # c_fc.weight is cut in two
+    cut = [s for s in segs if s.tensor == 8]
+    assert [(s.chunk, s.chunk_off, s.src_off, s.len) for s in cut] == \
+        [(0, 2_365_440, 0, S - 2_365_440), (1, 0, S - 2_365_440, 4_724_736 - S)]
+    last = segs[-1]
+    assert last.chunk == 1 and last.chunk_off + last.len == S - 1_300_736
+
+
+def test_layout_counts_of_the_large_workloads():
+    for name, want_chunks in (("gpt2_xl", 47), ("llama_7b", 101), ("llama_13b", 194)):
+        table, S = shapes.workload(name)
+        segs, n_chunks = B.pt_layout_dense([n for _, n in table], S)
+        assert n_chunks == want_chunks
+        assert sum(s.len for s in segs) == shapes.total_elems(table)
+        assert all(s.chunk_off % 8 == 0 and s.src_off % 8 == 0 for s in segs)     # vector path applies
+
+
+def test_argument_validation_without_a_gpu():
+    L = B.lib()
+    out = C.c_void_p()
+    assert L.pt_ctx_create(None, 0, 64, 1, None) == B.PT_ERR_INVALID_ARG
+    assert L.pt_ctx_create(C.byref(out), 7, 64, 1, None) == B.PT_ERR_INVALID_ARG
+    assert L.pt_ctx_create(C.byref(out), 0, 0, 1, None) == B.PT_ERR_INVALID_ARG
+    assert L.pt_ctx_create(C.byref(out), 0, 64, 0, None) == B.PT_ERR_INVALID_ARG
+    assert L.pt_ctx_create(C.byref(out), 0, 60, 1, None) == B.PT_ERR_ALIGNMENT
+    assert "multiple of 8" in B.pt_last_error(None)
+    bad = B.pt_scaler_cfg(0.5, 2.0, 0.5, 2000, 0)
+    assert L.pt_ctx_create(C.byref(out), 1, 64, 1, C.byref(bad)) == B.PT_ERR_INVALID_ARG
+    n = C.c_uint32()
+    sizes = (C.c_uint64 * 2)(5, 6)
+    assert L.pt_layout_dense(sizes, 2, 0, None, 0, C.byref(n), C.byref(n)) == B.PT_ERR_INVALID_ARG
+    assert L.pt_layout_dense(sizes, 2, 12, None, 0, C.byref(n), C.byref(n)) == B.PT_ERR_ALIGNMENT
+    assert L.pt_layout_dense(sizes, 2, 8, None, 0, None, C.byref(n)) == B.PT_ERR_INVALID_ARG
+    segs = (B.pt_segment * 1)()
+    assert L.pt_layout_dense(sizes, 2, 8, segs, 1, C.byref(n), C.byref(n)) == B.PT_ERR_INVALID_ARG  # cap too small
+    for fn in ("pt_step_end", "pt_ctx_set_state", "pt_stream_reserve"):
+        pass
+    assert L.pt_step_end(None, None) == B.PT_ERR_INVALID_ARG
+    assert L.pt_stream_reserve(None, 2) == B.PT_ERR_INVALID_ARG
+    assert L.pt_chunk_adamw_step(None, None, 0, 0, None, None, None, None, None, None) == B.PT_ERR_INVALID_ARG
+    assert L.pt_ctx_destroy(None) == B.PT_OK and L.pt_pack_plan_destroy(None) == B.PT_OK
+    with pytest.raises(B.PtError):
+        B.pt_layout_dense([1, 2], 12)

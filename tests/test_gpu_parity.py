@@ -1,0 +1,426 @@
+"""GPU parity: the HIP path (through the C-ABI binding) against the CPU oracle, element
+by element, on the same seeded inputs.
+
+Bars: pack/unpack and indexing bit-exact; gradient norm within relative 1e-5; fp32
+master/m/v within 1e-6 of the fp64 oracle (scale-aware, see tests/tolerance.py);
+16-bit parameters within one unit in the last place; and, with the device's own nine
+fp32 constants handed to the oracle's fp32 operation sequence, every array bit-exact.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from paper_2406_08334_amd import binding as B
+from paper_2406_08334_amd import shapes, synth
+from gpu_harness import ChunkedState, HP, hp_pair, same_bits, to_u16
+from tolerance import ScaleTracker, ulp16_distance
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    B.lib()                                    # fails loudly if the HIP library is missing
+    yield
+    torch.cuda.synchronize()
+
+
+def ulp_diff32(a, b):
+    a = np.asarray(a, np.float32).view(np.int32).astype(np.int64)
+    b = np.asarray(b, np.float32).view(np.int32).astype(np.int64)
+    return np.abs(a - b)
+
+
+# ------------------------------------------------------------------------------- pack
+
+RAGGED = [1, 3, 7, 8, 9, 17, 4099, 16384, 16385, 33, 100_003, 5, 2]      # odd sizes: misaligned sources
+ALIGNED = [8, 4096, 16384 * 3, 40, 8 * 12345, 64]
+
+
+@pytest.mark.parametrize("sizes,S", [(RAGGED, 16384 * 2 + 64), (RAGGED, 1024), (ALIGNED, 32768), ([5], 8),
+                                     ([], 64), ([64], 64)])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
+def test_pack_is_bit_exact_and_leaves_padding_alone(orc, sizes, S, dtype):
+    st = ChunkedState(sizes, S, dtype=dtype, init_params=False)
+    try:
+        n = st.N
+        bits = torch.randint(-32768, 32767, (max(n, 1),), dtype=torch.int16, device="cuda")
+        st.grad_src.view(torch.int16).copy_(bits)
+        st.g16.view(torch.int16).fill_(0x5A5A)               # sentinel: padding must survive
+        st.pack()
+        got = to_u16(st.g16)
+        src = to_u16(st.grad_src)[:n]
+        offs = np.cumsum([0] + list(sizes))
+        want = orc.pack_dense([src[offs[i]:offs[i + 1]] for i in range(len(sizes))], S, n_chunks=st.C)
+        assert same_bits(got.reshape(-1)[:n], want.reshape(-1)[:n])
+        assert np.all(got.reshape(-1)[n:] == 0x5A5A)
+        # inverse copy restores the tensors bit for bit
+        st.grad_src.zero_()
+        B.pt_chunk_unpack(st.ctx, st.plan, st.rows(st.g16))
+        assert same_bits(to_u16(st.grad_src)[:n], src)
+    finally:
+        st.close()
+
+
+def test_pack_gpt2_block_layout_against_oracle(orc):
+    table, S = shapes.workload("gpt2_block_768")
+    sizes = [n for _, n in table]
+    st = ChunkedState(sizes, S, init_params=False)
+    try:
+        st.set_grads(1)
+        st.pack()
+        src = to_u16(st.grad_src)
+        offs = np.cumsum([0] + sizes)
+        want = orc.pack_dense([src[offs[i]:offs[i + 1]] for i in range(len(sizes))], S)
+        assert same_bits(to_u16(st.g16), want)
+        assert not to_u16(st.g16)[1, S - 1_300_736:].any()
+    finally:
+        st.close()
+
+
+# ------------------------------------------------------------------------------- norm
+
+@pytest.mark.parametrize("dtype,scaler", [(torch.bfloat16, None), (torch.float16, B.pt_scaler_cfg(65536.0, 2.0, 0.5, 2000, 0))])
+@pytest.mark.parametrize("sizes,S", [(RAGGED, 32768 + 64), (ALIGNED, 32768), ([7_087_872], 1 << 22)])
+def test_norm_fused_and_standalone_match_oracle(orc, dtype, scaler, sizes, S):
+    st = ChunkedState(sizes, S, dtype=dtype, scaler=scaler, init_params=False)
+    try:
+        sigma = 65536.0 if scaler is not None else 1.0
+        st.set_grads(1, scale=sigma)
+        st.pack(); st.norm()
+        r1 = st.report()
+        g = to_u16(st.g16).reshape(-1)
+        want = orc.sqnorm(g, st.orc_dtype, loss_scale=sigma, block=S, threads=8)
+        assert r1.found_inf == 0
+        assert abs(r1.sqnorm - want) <= 1e-12 * want                 # bar is 1e-5 on the norm
+        assert abs(r1.norm - math.sqrt(want)) <= 1e-5 * math.sqrt(want)
+        st.norm(recompute=True)
+        r2 = st.report()
+        assert abs(r2.sqnorm - want) <= 1e-12 * want
+        # run-to-run bitwise reproducible
+        st.pack(); st.norm()
+        assert st.report().sqnorm == r1.sqnorm
+        st.norm(recompute=True)
+        assert st.report().sqnorm == r2.sqnorm
+    finally:
+        st.close()
+
+
+def test_norm_closed_forms(orc):
+    S = 1 << 20
+    st = ChunkedState([4 * S], S, init_params=False)          # 2^22 ones -> norm 2048 exactly
+    try:
+        st.grad_src.fill_(1.0)
+        st.pack(); st.norm()
+        assert st.report().norm == 2048.0
+        st.grad_src.zero_()
+        st.pack(); st.norm()
+        assert st.report().norm == 0.0 and st.report().found_inf == 0
+        st.grad_src[3 * S + 12345] = -0.375
+        st.pack(); st.norm()
+        assert st.report().norm == 0.375
+    finally:
+        st.close()
+
+
+@pytest.mark.parametrize("dtype,pats", [(torch.bfloat16, [0x7F80, 0xFF80, 0x7FC1]), (torch.float16, [0x7C00, 0xFC00, 0x7E00])])
+def test_nonfinite_is_found_wherever_it_sits(orc, dtype, pats):
+    sizes, S = RAGGED, 32768 + 64
+    st = ChunkedState(sizes, S, dtype=dtype, init_params=False)
+    try:
+        n = st.N
+        for k, pos in enumerate([0, 6, 16384 + 3, n - 1, n // 2, S - 1, S]):
+            st.set_grads(1)
+            st.grad_src.view(torch.int16)[pos] = np.array(pats[k % 3], np.uint16).view(np.int16).item()
+            st.pack(); st.norm()
+            assert st.report().found_inf == 1, pos
+            st.norm(recompute=True)
+            assert st.report().found_inf == 1, pos
+        st.set_grads(1)
+        st.grad_src.view(torch.int16)[5] = 0x7F7F if dtype == torch.bfloat16 else 0x7BFF   # largest finite
+        st.pack(); st.norm()
+        assert st.report().found_inf == 0
+    finally:
+        st.close()
+
+
+# ------------------------------------------------------------------------------- AdamW
+
+def run_oracle_f32seq(orc, consts, st_host, dtype):
+    orc.adamw_f32seq(consts, st_host["g16"], st_host["w"], st_host["m"], st_host["v"], st_host["p16"], dtype, threads=8)
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("S,C", [(4096 * 3 + 40, 3), (8, 2), (16384 * 8, 2), (4096, 1)])
+def test_adamw_kernel_isolated_is_bit_exact_against_f32_sequence(orc, dtype, S, C):
+    st = ChunkedState([S * C - 5], S, dtype=dtype)
+    try:
+        hp_b, hp_o, hpd = hp_pair()
+        host = st.host_state()
+        h64 = {k: a.copy() for k, a in host.items()}
+        trk = ScaleTracker(host["w"], host["m"], hpd)
+        gm = 0.0121
+        for t in (1, 2, 3):
+            st.set_grads(t)
+            st.pack()
+            B.pt_step_override(st.ctx, gm, False)
+            st.adamw(hp_b)
+            k = B.pt_update_consts_read(st.ctx)
+            st.end()
+            consts = np.array(list(k.c), dtype=np.float32)
+            want_c = orc.consts_f32(hp_o, t, float(np.float32(gm)))
+            assert ulp_diff32(consts, want_c).max() <= 1 and k.skip == 0
+            assert consts[8] == np.float32(gm)
+            g16 = to_u16(st.g16).reshape(-1)
+            host["g16"] = g16.copy()
+            run_oracle_f32seq(orc, consts, host, st.orc_dtype)
+            got = st.host_state()
+            for name in ("w", "m", "v", "p16"):
+                assert same_bits(got[name], host[name]), (name, t)
+            # and the fp64 oracle bounds both
+            orc.adamw_f64(hp_o, t, float(np.float32(gm)), g16, h64["w"], h64["m"], h64["v"], h64["p16"], st.orc_dtype, threads=8)
+            trk.advance(t, orc.decode16(g16, st.orc_dtype).astype(np.float64) * float(np.float32(gm)), h64["v"])
+            trk.check((got["w"], got["m"], got["v"]), (h64["w"], h64["m"], h64["v"]), tol=1e-6)
+            assert ulp16_distance(got["p16"], h64["p16"]).max() <= 1
+        # padding stayed exactly zero
+        assert not got["w"][-5:].any() and not got["m"][-5:].any() and not got["v"][-5:].any() and not got["p16"][-5:].any()
+    finally:
+        st.close()
+
+
+def test_adamw_golden_tiny_case(orc):
+    from test_oracle_golden import load_golden
+    rec = load_golden()
+    p16_0 = np.frombuffer(rec["p16_0"], dtype=np.uint16).copy()
+    n, S = p16_0.size, 16
+    st = ChunkedState([n], S, init_params=False)
+    try:
+        st.p16.view(-1)[:n].view(torch.int16).copy_(torch.from_numpy(p16_0.view(np.int16)).cuda())
+        st.w.copy_(st.p16.float())
+        hp_b, _, _ = hp_pair()
+        for s in (1, 2, 3):
+            g = np.frombuffer(rec[f"g16_{s}"], dtype=np.uint16).copy()
+            st.grad_src.view(torch.int16).copy_(torch.from_numpy(g.view(np.int16)).cuda())
+            rep = st.step(hp_b)
+            want_norm = np.frombuffer(rec[f"norm_{s}"], dtype=np.float64)[0]
+            assert abs(rep.norm - want_norm) <= 1e-12 * want_norm
+        got = st.host_state()
+        w = np.frombuffer(rec["w_final"], np.float32); m = np.frombuffer(rec["m_final"], np.float32)
+        v = np.frombuffer(rec["v_final"], np.float32); p = np.frombuffer(rec["p16_final"], np.uint16)
+        assert np.all(np.abs(got["v"][:n] - v) <= 1e-6 * np.abs(v))
+        assert np.all(np.abs(got["m"][:n] - m) <= 1e-6 * np.abs(m) + 1e-12)
+        assert np.all(np.abs(got["w"][:n] - w) <= 1e-6 * np.abs(w) + 1e-10)
+        assert ulp16_distance(got["p16"][:n], p).max() <= 1
+    finally:
+        st.close()
+
+
+def end_to_end(orc, sizes, S, dtype, steps, grad_std=1e-3, scaler_b=None, scaler_o=None, inf_step=None,
+               outlier_every=0, recompute_norm=False):
+    st = ChunkedState(sizes, S, dtype=dtype, scaler=scaler_b)
+    try:
+        hp_b, hp_o, hpd = hp_pair()
+        host = st.host_state()
+        ost = orc.new_state(scaler_o)
+        trk = ScaleTracker(host["w"], host["m"], hpd)
+        fa = {k: a.copy() for k, a in host.items()}            # fp32-sequence shadow fed with GPU scalars
+        reports = []
+        for s in range(1, steps + 1):
+            sigma = ost.loss_scale
+            st.set_grads(s, std=grad_std, scale=sigma, outlier_every=outlier_every)
+            if inf_step == s:
+                e = synth.pick_element(synth.SEED_INF, s, st.N)
+                st.grad_src.view(torch.int16)[e] = 0x7C00 if dtype == torch.float16 else 0x7F80
+            st.pack()
+            st.norm(recompute=recompute_norm)
+            st.adamw(hp_b)
+            rep = B.pt_step_report_read(st.ctx)
+            k = B.pt_update_consts_read(st.ctx)
+            st.end()
+            g16 = to_u16(st.g16).reshape(-1).copy()
+            orep = orc.step(hp_o, scaler_o, ost, g16, host["w"], host["m"], host["v"], host["p16"], S,
+                            st.orc_dtype, threads=8)
+            reports.append((rep, orep))
+            assert rep.found_inf == orep.found_inf
+            assert rep.loss_scale == orep.loss_scale_used
+            after = B.pt_step_report_read(st.ctx)
+            assert after.step == ost.t and after.loss_scale == ost.loss_scale and after.good_steps == (ost.good_steps if scaler_o else after.good_steps)
+            got = st.host_state()
+            if orep.found_inf:
+                assert k.skip == 1
+                for name in ("w", "m", "v", "p16"):
+                    assert same_bits(got[name], fa[name]), name       # untouched, bit for bit
+                continue
+            assert abs(rep.norm - orep.norm) <= 1e-5 * orep.norm
+            assert abs(rep.norm - orep.norm) <= 1e-12 * orep.norm     # what the fp64 reduction really gives
+            assert abs(rep.clip_coef - orep.clip_coef) <= 1e-12 * orep.clip_coef
+            assert abs(rep.grad_mult - orep.grad_mult) <= 6e-8 * orep.grad_mult
+            trk.advance(ost.t, orc.decode16(g16, st.orc_dtype).astype(np.float64) * orep.grad_mult, host["v"])
+            trk.check((got["w"], got["m"], got["v"]), (host["w"], host["m"], host["v"]), tol=1e-6)
+            assert ulp16_distance(got["p16"], host["p16"]).max() <= 1
+            consts = np.array(list(k.c), dtype=np.float32)
+            fa["g16"] = g16
+            run_oracle_f32seq(orc, consts, fa, st.orc_dtype)
+            for name in ("w", "m", "v", "p16"):
+                assert same_bits(got[name], fa[name]), (name, s)
+        return reports
+    finally:
+        st.close()
+
+
+def test_end_to_end_gpt2_block_bf16_three_steps(orc):
+    table, S = shapes.workload("gpt2_block_768")
+    reps = end_to_end(orc, [n for _, n in table], S, torch.bfloat16, steps=3)
+    for rep, orep in reps:
+        assert abs(orep.norm - 2.662) < 0.01 and rep.clip_coef < 1.0      # 1e-3 * sqrt(7,087,872)
+
+
+def test_end_to_end_ragged_with_outliers_and_recomputed_norm(orc):
+    reps = end_to_end(orc, RAGGED + [300_000], 65536 + 8, torch.bfloat16, steps=3, grad_std=1e-2,
+                      outlier_every=1000, recompute_norm=True)
+    assert all(r.clip_coef < 1.0 for r, _ in reps)
+
+
+def test_end_to_end_fp16_loss_scaling_with_a_skipped_step(orc):
+    sb = B.pt_scaler_cfg(65536.0, 2.0, 0.5, 2000, 0)
+    so = orc.ScalerCfg(65536.0, 2.0, 0.5, 2000, 1)
+    reps = end_to_end(orc, [1_000_000, 333, 4096 * 9], 1 << 18, torch.float16, steps=6, scaler_b=sb, scaler_o=so,
+                      inf_step=3)
+    assert [r.found_inf for r, _ in reps] == [0, 0, 1, 0, 0, 0]
+    assert [r.loss_scale for r, _ in reps] == [65536.0] * 3 + [32768.0] * 3
+
+
+def test_loss_scale_growth_on_device(orc):
+    sb = B.pt_scaler_cfg(4.0, 2.0, 0.5, 3, 0)
+    st = ChunkedState([256], 64, dtype=torch.float16, scaler=sb, init_params=False)
+    try:
+        hp_b, _, _ = hp_pair()
+        scales = []
+        for _ in range(7):
+            st.step(hp_b)
+            scales.append(st.report().loss_scale)
+        assert scales == [4.0, 4.0, 8.0, 8.0, 8.0, 16.0, 16.0]
+        st.grad_src.view(torch.int16)[3] = np.array(0xFC00, np.uint16).view(np.int16).item()
+        for want in (8.0, 4.0, 2.0, 1.0, 1.0):
+            st.step(hp_b)
+            r = st.report()
+            assert r.loss_scale == want and r.good_steps == 0 and r.step == 7
+        B.pt_ctx_set_state(st.ctx, 11, 128.0, 2)
+        r = st.report()
+        assert (r.step, r.loss_scale, r.good_steps) == (11, 128.0, 2)
+    finally:
+        st.close()
+
+
+# ------------------------------------------------------------------- streamed == resident
+
+def run_mixed(sizes, S, n_persist, n_slots, steps, dtype=torch.bfloat16, scaler=None, inf_step=None):
+    st = ChunkedState(sizes, S, dtype=dtype, scaler=scaler)
+    try:
+        hp_b, _, _ = hp_pair()
+        C = st.C
+        host = {}
+        if n_persist < C:
+            B.pt_stream_reserve(st.ctx, n_slots)
+            for name, arena in (("g16", st.g16), ("p16", st.p16), ("w", st.w), ("m", st.m), ("v", st.v)):
+                host[name] = [torch.empty(S, dtype=arena.dtype).pin_memory() for _ in range(n_persist, C)]
+            for name, arena in (("p16", st.p16), ("w", st.w), ("m", st.m), ("v", st.v)):
+                for i, c in enumerate(range(n_persist, C)):
+                    host[name][i].copy_(arena[c])
+                arena[n_persist:].fill_(7)                      # device copies of streamed chunks are not used
+        for s in range(1, steps + 1):
+            sigma = 65536.0 if scaler is not None else 1.0
+            st.set_grads(s, scale=sigma)
+            if inf_step == s:
+                st.grad_src.view(torch.int16)[st.N // 3] = 0x7C00 if dtype == torch.float16 else 0x7F80
+            st.pack()                                            # partials are taken on the GPU ...
+            for i, c in enumerate(range(n_persist, C)):          # ... before the chunk is offloaded
+                host["g16"][i].copy_(st.g16[c])
+            torch.cuda.synchronize()
+            st.norm()
+            if n_persist < C:
+                B.pt_chunk_stream_step(st.ctx, hp_b, n_persist, C - n_persist, host["g16"], host["w"], host["m"],
+                                       host["v"], host["p16"])
+            if n_persist > 0:
+                st.adamw(hp_b, 0, n_persist)
+            st.end()
+        torch.cuda.synchronize()
+        out = {}
+        for name, arena in (("p16", st.p16), ("w", st.w), ("m", st.m), ("v", st.v)):
+            full = arena.clone()
+            for i, c in enumerate(range(n_persist, C)):
+                full[c].copy_(host[name][i])
+            out[name] = full.cpu()
+        out["report"] = st.report()
+        return out
+    finally:
+        st.close()
+
+
+@pytest.mark.parametrize("dtype,scaler,inf_step", [(torch.bfloat16, None, None),
+                                                   (torch.float16, B.pt_scaler_cfg(65536.0, 2.0, 0.5, 2000, 0), 2)])
+def test_streamed_chunks_give_the_same_bits_as_resident_ones(dtype, scaler, inf_step):
+    sizes, S = [6 * 40_000 - 24], 40_000                        # 6 chunks, last one padded
+    ref = run_mixed(sizes, S, 6, 2, steps=3, dtype=dtype, scaler=scaler, inf_step=inf_step)
+    for n_persist, n_slots in ((3, 2), (0, 2), (0, 3), (2, 3), (5, 2)):
+        got = run_mixed(sizes, S, n_persist, n_slots, steps=3, dtype=dtype, scaler=scaler, inf_step=inf_step)
+        for name in ("p16", "w", "m", "v"):
+            assert torch.equal(got[name].view(torch.int16 if got[name].element_size() == 2 else torch.int32),
+                               ref[name].view(torch.int16 if ref[name].element_size() == 2 else torch.int32)), \
+                (name, n_persist, n_slots)
+        assert got["report"].step == ref["report"].step and got["report"].loss_scale == ref["report"].loss_scale
+
+
+# ------------------------------------------------------------------------------- errors
+
+def test_error_paths_return_codes_and_leave_the_context_usable():
+    st = ChunkedState([1000], 512, init_params=True)
+    try:
+        hp_b, _, _ = hp_pair()
+        with pytest.raises(B.PtError) as e:
+            st.adamw(hp_b)                                       # no finalized norm yet
+        assert e.value.status == B.PT_ERR_STATE
+        with pytest.raises(B.PtError) as e:
+            B.pt_chunk_grad_sqnorm(st.ctx, None, 1, 2, True)     # range outside the context
+        assert e.value.status == B.PT_ERR_INVALID_ARG
+        st.pack(); st.norm()
+        with pytest.raises(B.PtError) as e:
+            B.pt_chunk_adamw_step(st.ctx, hp_b, 0, 3, st.rows(st.g16), st.rows(st.w), st.rows(st.m), st.rows(st.v),
+                                  st.rows(st.p16))
+        assert e.value.status == B.PT_ERR_INVALID_ARG
+        bad = [st.w[0][1:], st.w[1]]                             # 4-byte aligned only
+        with pytest.raises(B.PtError) as e:
+            B.pt_chunk_adamw_step(st.ctx, hp_b, 0, 2, st.rows(st.g16), bad, st.rows(st.m), st.rows(st.v), st.rows(st.p16))
+        assert e.value.status == B.PT_ERR_ALIGNMENT
+        with pytest.raises(B.PtError) as e:
+            B.pt_chunk_adamw_step(st.ctx, hp_b, 0, 2, st.rows(st.g16), [st.w[0], None], st.rows(st.m), st.rows(st.v),
+                                  st.rows(st.p16))
+        assert e.value.status == B.PT_ERR_INVALID_ARG
+        with pytest.raises(B.PtError) as e:
+            B.pt_chunk_stream_step(st.ctx, hp_b, 0, 1, [st.g16[0]], [st.w[0]], [st.m[0]], [st.v[0]], [st.p16[0]])
+        assert e.value.status == B.PT_ERR_STATE                  # no chunk buffers reserved
+        with pytest.raises(B.PtError) as e:
+            B.pt_stream_reserve(st.ctx, 1)
+        assert e.value.status == B.PT_ERR_INVALID_ARG
+        # overlapping segments / overrun are refused when the plan is built
+        s0 = B.pt_segment(st.grad_src.data_ptr(), 0, 100, 0, 0, 0)
+        s1 = B.pt_segment(st.grad_src.data_ptr(), 0, 100, 50, 0, 0)
+        with pytest.raises(B.PtError) as e:
+            B.pt_pack_plan_create(st.ctx, [s0, s1])
+        assert e.value.status == B.PT_ERR_INVALID_ARG and "overlap" in str(e.value)
+        s2 = B.pt_segment(st.grad_src.data_ptr(), 0, 100, 500, 0, 0)
+        with pytest.raises(B.PtError) as e:
+            B.pt_pack_plan_create(st.ctx, [s2])
+        assert e.value.status == B.PT_ERR_INVALID_ARG and "overruns" in str(e.value)
+        with pytest.raises(B.PtError) as e:
+            B.pt_chunk_pack_grads(st.ctx, st.plan, [None, None])
+        assert e.value.status == B.PT_ERR_INVALID_ARG
+        # after all that the step still completes normally
+        st.adamw(hp_b); st.end()
+        assert st.report().step == 1
+    finally:
+        st.close()
