@@ -70,6 +70,10 @@ __device__ __forceinline__ uint32_t encode16(float x) {
     if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x0040u;  // NaN stays NaN
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;                    // round to nearest, ties to even
   } else {
+    // The recast rounds the STORED fp32 master weight.  Without this barrier the compiler
+    // folds the producing fma and the conversion into one mixed-precision fma that rounds
+    // the exact result straight to fp16, which can differ from RNE16(RNE32(.)) by one ulp.
+    asm volatile("" : "+v"(x));
     __half_raw r = __half_raw(__float2half_rn(x));
     return (uint32_t)r.x;
   }

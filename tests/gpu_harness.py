@@ -110,3 +110,16 @@ class ChunkedState:
 def same_bits(a: np.ndarray, b: np.ndarray) -> bool:
     a = np.ascontiguousarray(a); b = np.ascontiguousarray(b)
     return a.dtype == b.dtype and a.shape == b.shape and a.tobytes() == b.tobytes()
+
+
+def assert_same_bits(got: np.ndarray, want: np.ndarray, label):
+    """Bit-for-bit equality with a useful message (count and first mismatches)."""
+    if same_bits(got, want):
+        return
+    assert got.shape == want.shape and got.dtype == want.dtype, (label, got.shape, want.shape)
+    u = np.uint16 if got.dtype.itemsize == 2 else np.uint32
+    gi, wi = got.reshape(-1).view(u), want.reshape(-1).view(u)
+    idx = np.flatnonzero(gi != wi)
+    k = idx[:6]
+    raise AssertionError(f"{label}: {idx.size} of {gi.size} words differ; first at {k.tolist()} "
+                         f"got {[hex(int(x)) for x in gi[k]]} want {[hex(int(x)) for x in wi[k]]}")

@@ -49,3 +49,28 @@ def ulp16_distance(a, b):
         x = np.asarray(x, dtype=np.uint16).astype(np.int32)
         return np.where(x & 0x8000, -(x & 0x7FFF), x & 0x7FFF)
     return np.abs(order(a) - order(b))
+
+
+def ulp16(x, fp16: bool):
+    """Spacing of the 16-bit format at magnitude |x| (bf16: 8 significand bits; fp16: 11, emin -14)."""
+    ax = np.abs(np.asarray(x, dtype=np.float64))
+    _, e = np.frexp(np.where(ax > 0, ax, 1.0))
+    e = e - 1
+    if fp16:
+        return np.ldexp(1.0, np.maximum(e, -14) - 10)
+    return np.ldexp(1.0, np.maximum(e, -126) - 7)
+
+
+def check_p16(got_p_val, want_p_val, want_w, W, fp16: bool, tol=1e-6):
+    """16-bit parameters: "within one ulp" read in the value domain as
+    |p_got - p_want| <= ulp16(w) + tol * W: both sides round their own fp32 master weight
+    (half an ulp each) and the master weights themselves may differ by tol * W (see
+    ScaleTracker).  Away from cancellation in w this is the plain one-ulp bar.
+    Returns the number of elements whose patterns differ by more than one ulp."""
+    gp = np.asarray(got_p_val, dtype=np.float64)
+    wp = np.asarray(want_p_val, dtype=np.float64)
+    d = np.abs(gp - wp)
+    u = ulp16(want_w, fp16)
+    bad = d > u * 1.0000001 + tol * W
+    assert not bad.any(), f"p16: {int(bad.sum())} elements beyond ulp16 + {tol} x scale"
+    return int((d > u * 1.0000001).sum())
