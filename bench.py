@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the chunked model-state hot path on one MI355X.
+
+One "step" = pt_chunk_pack_grads -> pt_chunk_grad_sqnorm(finalize) -> pt_chunk_adamw_step
+-> pt_step_end over a whole synthetic model state that is resident in HBM (default: the
+LLaMA-7B-shaped state, 101 chunks of 2^26 elements, bf16 params/grads + fp32 master/m/v).
+Prints ONE JSON line: whole-step algorithmic GB/s and ms/step, the roofline of the dominant
+kernel (the fused AdamW update, 28 B/element) measured with events on the launch stream,
+and the CPU oracle timed on a bounded sample of the same state.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama_7b]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "chunked AdamW step: achieved HBM GB/s (% of peak) + ms/step, 7B-shaped state"
+HBM_PEAK_GBPS = 8000.0
+HP = dict(lr=1e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, max_norm=1.0)
+ADAMW_BYTES_PER_ELEM = 28          # read g16 2 + w,m,v 12 ; write w,m,v 12 + p16 2
+PACK_BYTES_PER_ELEM = 4            # read 2 + write 2
+
+# HBM traffic of one AdamW launch from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by the
+# same counters on pt_calib_copy); filled from the summaries under profiles/.  bytes per launch.
+MEASURED_TRAFFIC = {
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama_7b", help="llama_7b | gpt2_xl | gpt2_block_768")
+    ap.add_argument("--grad-sets", type=int, default=3, help="distinct pre-generated gradient sets, rotated")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-chunks", type=int, default=4)
+    ap.add_argument("--calib", action="store_true", help="also time a bare copy kernel (attainable HBM rate)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "run it with --gpus 1. How the path would shard is described in DESIGN.md.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2406_08334_amd import binding as B
+    from paper_2406_08334_amd import shapes, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    B.lib()
+
+    table, S = shapes.workload(args.workload)
+    sizes = [n for _, n in table]
+    N = sum(sizes)
+    segs, C = B.pt_layout_dense(sizes, S)
+    N_pad = C * S
+    n_sets = max(1, min(args.grad_sets, args.steps + args.warmup))
+    log(f"[bench] workload {args.workload}: {N:,} elements, {C} chunks of {S:,}; "
+        f"state {16 * N_pad / 1e9:.2f} GB + {n_sets} gradient sets of {2 * N / 1e9:.2f} GB")
+
+    t0 = time.time()
+    ctx = B.pt_ctx_create(B.PT_BF16, S, C, None)
+    g16 = torch.zeros(C, S, dtype=torch.bfloat16, device=dev)
+    p16 = torch.zeros(C, S, dtype=torch.bfloat16, device=dev)
+    synth.normal_16(synth.SEED_PARAMS, 0, 0, 0, N, 0.02, torch.bfloat16, dev, out=p16.view(-1)[:N])
+    w = torch.empty(C, S, dtype=torch.float32, device=dev)
+    for c in range(C):
+        w[c].copy_(p16[c])
+    m = torch.zeros(C, S, dtype=torch.float32, device=dev)
+    v = torch.zeros(C, S, dtype=torch.float32, device=dev)
+    offs = np.cumsum([0] + sizes[:-1]).tolist()
+    grad_sets, plans = [], []
+    for k in range(n_sets):
+        gs = torch.empty(N, dtype=torch.bfloat16, device=dev)
+        synth.normal_16(synth.SEED_GRADS, k + 1, 0, 0, N, 1e-3, torch.bfloat16, dev, out=gs)
+        for s in segs:
+            s.src = gs.data_ptr() + 2 * offs[s.tensor]
+        grad_sets.append(gs)
+        plans.append(B.pt_pack_plan_create(ctx, segs))
+    torch.cuda.synchronize()
+    log(f"[bench] state generated in {time.time() - t0:.1f} s")
+
+    hp = B.hparams(**HP)
+    rows = lambda a: [a[c] for c in range(C)]
+    r_g, r_w, r_m, r_v, r_p = rows(g16), rows(w), rows(m), rows(v), rows(p16)
+    stream = torch.cuda.current_stream()
+
+    # ---- CPU baseline input: the sample chunks' state BEFORE any step (oracle runs afterwards)
+    n_cpu = 0 if args.no_cpu_baseline else max(0, min(args.cpu_sample_chunks, C))
+    cpu_in = None
+    if n_cpu:
+        u16 = lambda t: t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16).reshape(-1).copy()
+        B.pt_chunk_pack_grads(ctx, plans[0], r_g, stream)
+        torch.cuda.synchronize()
+        cpu_in = dict(g=u16(g16[:n_cpu]), p=u16(p16[:n_cpu]), w=w[:n_cpu].cpu().numpy().reshape(-1).copy(),
+                      src=[u16(grad_sets[0][:n_cpu * S])])
+
+    def one_step(k, ev=None):
+        B.pt_chunk_pack_grads(ctx, plans[k % n_sets], r_g, stream)
+        if ev: ev[0].record(stream)
+        B.pt_chunk_grad_sqnorm(ctx, None, 0, C, True, stream)
+        if ev: ev[1].record(stream)
+        B.pt_chunk_adamw_step(ctx, hp, 0, C, r_g, r_w, r_m, r_v, r_p, stream)
+        if ev: ev[2].record(stream)
+        B.pt_step_end(ctx, stream)
+
+    for k in range(args.warmup):
+        one_step(k)
+    torch.cuda.synchronize()
+
+    K = args.steps
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+    ev_begin = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for k in range(K):
+        ev_begin[k].record(stream)
+        one_step(args.warmup + k, evs[k])
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t_start
+
+    rep = B.pt_step_report_read(ctx, stream)
+    ms_step = 1e3 * t_total / K
+    pack_ms = [ev_begin[k].elapsed_time(evs[k][0]) for k in range(K)]
+    norm_ms = [evs[k][0].elapsed_time(evs[k][1]) for k in range(K)]
+    adamw_ms = [evs[k][1].elapsed_time(evs[k][2]) for k in range(K)]
+    mean = lambda x: float(sum(x) / len(x))
+    step_bytes = PACK_BYTES_PER_ELEM * N + ADAMW_BYTES_PER_ELEM * N_pad
+    adamw_bytes = ADAMW_BYTES_PER_ELEM * N_pad
+    achieved = adamw_bytes / (mean(adamw_ms) * 1e-3) / 1e9
+    value = step_bytes / (ms_step * 1e-3) / 1e9
+
+    out = {
+        "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {N} elements in {C} chunks of {S}, all GPU-resident, "
+                               "bf16 params/grads N(0,0.02)/N(0,1e-3), fp32 master/m/v, AdamW lr 1e-4 betas (0.9,0.95) "
+                               "eps 1e-8 wd 0.1 clip 1.0",
+                   "chunk_elems": S, "n_chunks": C, "elements": N, "padded_elements": N_pad,
+                   "step_bytes": step_bytes, "grad_sets": n_sets},
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "kernels_ms": {"pack_grads+chunk_reduce": round(mean(pack_ms), 4), "finalize": round(mean(norm_ms), 4),
+                       "adamw(+prepare)": round(mean(adamw_ms), 4)},
+        "step_report": {"norm": rep.norm, "clip_coef": rep.clip_coef, "found_inf": rep.found_inf, "step": rep.step},
+        "roofline": {"kernel": "k_adamw<bf16>", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": MEASURED_TRAFFIC.get(args.workload),
+                     "bytes_per_launch": adamw_bytes, "avg_launch_ms": round(mean(adamw_ms), 4)},
+    }
+
+    if args.calib:
+        a, b = m, v          # same-size arenas; contents are restored by copying back
+        scratch = torch.empty_like(a[0])
+        nbytes = a[0].numel() * 4
+        times = []
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for c in range(min(C, 16)):
+                B.pt_calib_copy(scratch, a[c], nbytes, stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1))
+        out["hbm_copy_GBps"] = round(2 * nbytes * min(C, 16) / (min(times) * 1e-3) / 1e9, 1)
+
+    if n_cpu:
+        import oracle as O
+        threads = O.hardware_threads()
+        hp_o = O.Hparams(**HP)
+        n_el = n_cpu * S
+        ow, om, ov, op = cpu_in["w"], np.zeros(n_el, np.float32), np.zeros(n_el, np.float32), cpu_in["p"]
+        ost = O.new_state(None)
+        reps = 2
+        t_cpu = time.perf_counter()
+        for _ in range(reps):
+            chunks = O.pack_dense(cpu_in["src"], S, n_chunks=n_cpu)
+            O.step(hp_o, None, ost, chunks.reshape(-1), ow, om, ov, op, S, O.BF16, threads=threads)
+        t_cpu = (time.perf_counter() - t_cpu) / reps
+        cpu_bytes = (PACK_BYTES_PER_ELEM + ADAMW_BYTES_PER_ELEM) * n_el
+        out["cpu_baseline"] = {"value": round(cpu_bytes / t_cpu / 1e9, 3), "unit": "GB/s", "cores": threads,
+                               "kind": "oracle",
+                               "sample": f"first {n_cpu} chunks ({n_el} elements) of the same state: oracle pack + "
+                                         f"scan + fp64 norm + clip + fp64-evaluated AdamW, {reps} steps, "
+                                         f"{t_cpu * 1e3:.1f} ms/step; the update is threaded, pack and the "
+                                         f"non-finite scan are serial",
+                               "ms_per_step_sample": round(t_cpu * 1e3, 2)}
+
+    for p in plans:
+        B.pt_pack_plan_destroy(p)
+    B.pt_ctx_destroy(ctx)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

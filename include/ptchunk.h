@@ -241,6 +241,12 @@ int pt_update_consts_read(pt_ctx* ctx, pt_update_consts* out, void* stream);
  * skips if found_inf != 0.  For kernel-isolated tests. */
 int pt_step_override(pt_ctx* ctx, float grad_mult, int32_t found_inf, void* stream);
 
+/* ---- measurement aid ----------------------------------------------------------------
+ * A plain device-to-device streaming copy of `bytes` bytes (16-byte aligned pointers
+ * and size): the known-size kernel against which hardware traffic counters and the
+ * attainable HBM rate of a box are calibrated.  Not part of the optimizer path. */
+int pt_calib_copy(void* dst, const void* src, uint64_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

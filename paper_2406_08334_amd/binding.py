@@ -20,7 +20,7 @@ EXPORTS = [
     "pt_version", "pt_status_string", "pt_last_error", "pt_ctx_create", "pt_ctx_destroy", "pt_ctx_set_state",
     "pt_layout_dense", "pt_pack_plan_create", "pt_pack_plan_destroy", "pt_chunk_pack_grads", "pt_chunk_unpack",
     "pt_chunk_grad_sqnorm", "pt_chunk_adamw_step", "pt_stream_reserve", "pt_chunk_stream_step", "pt_step_end",
-    "pt_step_report_read", "pt_update_consts_read", "pt_step_override",
+    "pt_step_report_read", "pt_update_consts_read", "pt_step_override", "pt_calib_copy",
 ]
 
 
@@ -95,6 +95,7 @@ def lib():
         L.pt_step_report_read.argtypes = [vp, C.POINTER(pt_step_report), vp]
         L.pt_update_consts_read.argtypes = [vp, C.POINTER(pt_update_consts), vp]
         L.pt_step_override.argtypes = [vp, C.c_float, i32, vp]
+        L.pt_calib_copy.argtypes = [vp, vp, u64, vp]
         for name in EXPORTS:
             if name not in ("pt_version", "pt_status_string", "pt_last_error"):
                 getattr(L, name).restype = C.c_int
@@ -251,3 +252,7 @@ def pt_update_consts_read(ctx, stream=None) -> pt_update_consts:
 def pt_step_override(ctx, grad_mult: float, found_inf: bool, stream=None):
     _check(lib().pt_step_override(ctx, float(grad_mult), 1 if found_inf else 0, _stream(stream)),
            "pt_step_override", ctx)
+
+
+def pt_calib_copy(dst, src, nbytes: int, stream=None):
+    _check(lib().pt_calib_copy(_addr(dst), _addr(src), int(nbytes), _stream(stream)), "pt_calib_copy")

@@ -9,6 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libptchunk.so")
+PROBE = os.path.join(HERE, "ptchunk_probe")
 SOURCES = ["pt_ctx.hip", "pt_norm.hip", "pt_pack.hip", "pt_adamw.hip", "pt_stream.hip"]
 
 FLAGS = [
@@ -43,6 +44,15 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed")
     if verbose and err.strip():
         print(err)
+    # the Python-free driver of the C ABI (used under rocprofv3 for hardware counters)
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O2", "-std=c++17", "-I", os.path.join(ROOT, "include"), os.path.join(CSRC, "pt_probe.cpp"),
+           "-o", PROBE, "-L", HERE, "-lptchunk", "-Wl,-rpath,$ORIGIN"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        sys.stderr.write(res.stdout + res.stderr)
+        raise RuntimeError("hipcc failed on pt_probe.cpp")
     return LIB
 
 

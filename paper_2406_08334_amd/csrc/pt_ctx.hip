@@ -286,3 +286,35 @@ extern "C" int pt_layout_dense(const uint64_t* tensor_elems, uint32_t n_tensors,
   *n_chunks = uint32_t((pos + chunk_elems - 1) / chunk_elems);
   return PT_OK;
 }
+
+// ---- measurement aid: a plain streaming copy ----------------------------------------------------
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+__global__ void __launch_bounds__(256) k_calib_copy(u32x4_t* __restrict__ dst, const u32x4_t* __restrict__ src,
+                                                    uint64_t n_vec) {
+  const uint64_t stride = uint64_t(gridDim.x) * 256 * 4;
+  for (uint64_t i = uint64_t(blockIdx.x) * 256 * 4 + threadIdx.x; i < n_vec; i += stride) {
+    u32x4_t q[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (i + r * 256 < n_vec) q[r] = __builtin_nontemporal_load(src + i + r * 256);
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (i + r * 256 < n_vec) __builtin_nontemporal_store(q[r], dst + i + r * 256);
+  }
+}
+
+extern "C" int pt_calib_copy(void* dst, const void* src, uint64_t bytes, void* stream) {
+  if (!dst || !src) return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_calib_copy: NULL pointer");
+  if ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src) | bytes) & 15)
+    return pt_fail(nullptr, PT_ERR_ALIGNMENT, "pt_calib_copy: pointers and size must be multiples of 16");
+  if (bytes == 0) return PT_OK;
+  uint64_t n_vec = bytes / 16;
+  uint64_t blocks = (n_vec + 1023) / 1024;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  hipLaunchKernelGGL(k_calib_copy, dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream,
+                     (u32x4_t*)dst, (const u32x4_t*)src, n_vec);
+  if (hipGetLastError() != hipSuccess) return pt_fail(nullptr, PT_ERR_HIP, "pt_calib_copy: launch failed");
+  return PT_OK;
+}

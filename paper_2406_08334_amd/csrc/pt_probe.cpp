@@ -1,0 +1,141 @@
+// ptchunk_probe: a plain C++ driver of the C-ABI library, without Python or PyTorch.
+//
+// Runs `steps` optimizer steps (pack -> norm -> AdamW -> step end) over a synthetic state
+// of n_chunks x chunk_elems elements, then `copies` launches of the calibration copy over
+// one fp32 chunk, and prints hipEvent timings.  It exists so that hardware counters can be
+// collected with `rocprofv3 --pmc ... -- ./ptchunk_probe ...` on a process that holds
+// nothing but this library, and doubles as a usage example of the boundary.
+//
+//   ptchunk_probe [chunk_elems=67108864] [n_chunks=101] [steps=3] [copies=4]
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "ptchunk.h"
+
+#define CHECK_HIP(x)                                                                        \
+  do {                                                                                      \
+    hipError_t err_ = (x);                                                                  \
+    if (err_ != hipSuccess) {                                                               \
+      fprintf(stderr, "%s failed: %s\n", #x, hipGetErrorString(err_));                      \
+      return 1;                                                                             \
+    }                                                                                       \
+  } while (0)
+#define CHECK_PT(ctx, x)                                                                    \
+  do {                                                                                      \
+    int rc = (x);                                                                           \
+    if (rc != PT_OK) {                                                                      \
+      fprintf(stderr, "%s -> %s: %s\n", #x, pt_status_string(rc), pt_last_error(ctx));      \
+      return 1;                                                                             \
+    }                                                                                       \
+  } while (0)
+
+static uint16_t bf16_of(float x) {
+  uint32_t u;
+  memcpy(&u, &x, 4);
+  return uint16_t((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
+int main(int argc, char** argv) {
+  const uint64_t S = argc > 1 ? strtoull(argv[1], nullptr, 10) : (1ull << 26);
+  const uint32_t C = argc > 2 ? (uint32_t)atoi(argv[2]) : 101;
+  const int steps = argc > 3 ? atoi(argv[3]) : 3;
+  const int copies = argc > 4 ? atoi(argv[4]) : 4;
+  printf("probe: %u chunks of %llu elements, %d steps, %d copies\n", C, (unsigned long long)S, steps, copies);
+
+  pt_ctx* ctx = nullptr;
+  CHECK_PT(nullptr, pt_ctx_create(&ctx, PT_BF16, S, C, nullptr));
+
+  // one chunk of pseudo-random host data (LCG -> roughly uniform in +-1e-3 / +-0.03), replicated
+  std::vector<uint16_t> hg(S), hp(S);
+  std::vector<float> hw(S);
+  uint32_t r = 12345u;
+  for (uint64_t i = 0; i < S; ++i) {
+    r = r * 1664525u + 1013904223u;
+    float u1 = (float)((r >> 8) & 0xffff) / 32768.0f - 1.0f;
+    r = r * 1664525u + 1013904223u;
+    float u2 = (float)((r >> 8) & 0xffff) / 32768.0f - 1.0f;
+    hg[i] = bf16_of(1.7e-3f * u1);
+    hp[i] = bf16_of(0.035f * u2);
+    uint32_t b = uint32_t(hp[i]) << 16;
+    memcpy(&hw[i], &b, 4);
+  }
+
+  std::vector<void*> src(C), g(C), p(C);
+  std::vector<float*> w(C), m(C), v(C);
+  for (uint32_t c = 0; c < C; ++c) {
+    CHECK_HIP(hipMalloc(&src[c], 2 * S));
+    CHECK_HIP(hipMalloc(&g[c], 2 * S));
+    CHECK_HIP(hipMalloc(&p[c], 2 * S));
+    CHECK_HIP(hipMalloc((void**)&w[c], 4 * S));
+    CHECK_HIP(hipMalloc((void**)&m[c], 4 * S));
+    CHECK_HIP(hipMalloc((void**)&v[c], 4 * S));
+    CHECK_HIP(hipMemcpy(src[c], hg.data(), 2 * S, hipMemcpyHostToDevice));
+    CHECK_HIP(hipMemcpy(p[c], hp.data(), 2 * S, hipMemcpyHostToDevice));
+    CHECK_HIP(hipMemcpy(w[c], hw.data(), 4 * S, hipMemcpyHostToDevice));
+    CHECK_HIP(hipMemset(m[c], 0, 4 * S));
+    CHECK_HIP(hipMemset(v[c], 0, 4 * S));
+    CHECK_HIP(hipMemset(g[c], 0, 2 * S));
+  }
+  // one "tensor" per chunk, filling it completely
+  std::vector<pt_segment> segs(C);
+  for (uint32_t c = 0; c < C; ++c) segs[c] = pt_segment{src[c], 0, S, 0, c, c};
+  pt_pack_plan* plan = nullptr;
+  CHECK_PT(ctx, pt_pack_plan_create(ctx, segs.data(), C, &plan));
+
+  hipStream_t st;
+  CHECK_HIP(hipStreamCreate(&st));
+  hipEvent_t e[4];
+  for (auto& x : e) CHECK_HIP(hipEventCreate(&x));
+  const pt_hparams hpar{1e-4, 0.9, 0.95, 1e-8, 0.1, 1.0};
+
+  for (int s = 0; s < steps; ++s) {
+    CHECK_HIP(hipEventRecord(e[0], st));
+    CHECK_PT(ctx, pt_chunk_pack_grads(ctx, plan, g.data(), st));
+    CHECK_HIP(hipEventRecord(e[1], st));
+    CHECK_PT(ctx, pt_chunk_grad_sqnorm(ctx, nullptr, 0, C, 1, st));
+    CHECK_HIP(hipEventRecord(e[2], st));
+    CHECK_PT(ctx, pt_chunk_adamw_step(ctx, &hpar, 0, C, g.data(), w.data(), m.data(), v.data(), p.data(), st));
+    CHECK_HIP(hipEventRecord(e[3], st));
+    CHECK_PT(ctx, pt_step_end(ctx, st));
+    CHECK_HIP(hipStreamSynchronize(st));
+    float t_pack, t_norm, t_adamw;
+    CHECK_HIP(hipEventElapsedTime(&t_pack, e[0], e[1]));
+    CHECK_HIP(hipEventElapsedTime(&t_norm, e[1], e[2]));
+    CHECK_HIP(hipEventElapsedTime(&t_adamw, e[2], e[3]));
+    pt_step_report rep;
+    CHECK_PT(ctx, pt_step_report_read(ctx, &rep, st));
+    const double n = double(S) * C;
+    printf("step %d: pack %.3f ms (%.0f GB/s)  finalize %.3f ms  adamw %.3f ms (%.0f GB/s)  norm %.6f step %d\n", s,
+           t_pack, 4.0 * n / t_pack / 1e6, t_norm, t_adamw, 28.0 * n / t_adamw / 1e6, rep.norm, rep.step);
+  }
+  // standalone norm over all chunks (reads 2 bytes per element)
+  {
+    CHECK_HIP(hipEventRecord(e[0], st));
+    CHECK_PT(ctx, pt_chunk_grad_sqnorm(ctx, g.data(), 0, C, 1, st));
+    CHECK_HIP(hipEventRecord(e[1], st));
+    CHECK_HIP(hipStreamSynchronize(st));
+    float t;
+    CHECK_HIP(hipEventElapsedTime(&t, e[0], e[1]));
+    printf("sqnorm standalone: %.3f ms (%.0f GB/s)\n", t, 2.0 * double(S) * C / t / 1e6);
+    CHECK_PT(ctx, pt_step_end(ctx, st));
+  }
+  for (int k = 0; k < copies; ++k) {
+    CHECK_HIP(hipEventRecord(e[0], st));
+    CHECK_PT(nullptr, pt_calib_copy(m[(k + 1) % C], v[k % C], 4 * S, st));
+    CHECK_HIP(hipEventRecord(e[1], st));
+    CHECK_HIP(hipStreamSynchronize(st));
+    float t;
+    CHECK_HIP(hipEventElapsedTime(&t, e[0], e[1]));
+    printf("calib copy %d: %llu bytes read + written in %.3f ms (%.0f GB/s)\n", k, (unsigned long long)(4 * S), t,
+           8.0 * double(S) / t / 1e6);
+  }
+  CHECK_PT(ctx, pt_pack_plan_destroy(plan));
+  CHECK_PT(ctx, pt_ctx_destroy(ctx));
+  printf("probe done\n");
+  return 0;
+}
