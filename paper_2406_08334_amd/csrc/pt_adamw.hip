@@ -16,12 +16,45 @@
 
 namespace {
 
-constexpr int AW_THREADS = 256;
-constexpr int AW_UNROLL = 4;
-constexpr uint32_t AW_TILE_UNITS = AW_THREADS * AW_UNROLL;  // 4-element units per tile (4096 elements)
+#ifndef PT_AW_THREADS
+#define PT_AW_THREADS 256
+#endif
+#ifndef PT_AW_UNROLL
+#define PT_AW_UNROLL 4
+#endif
+#ifndef PT_AW_NT
+#define PT_AW_NT 1        // non-temporal hints: every byte is touched once per step
+#endif
+
+constexpr int AW_THREADS = PT_AW_THREADS;
+constexpr int AW_UNROLL = PT_AW_UNROLL;
+constexpr uint32_t AW_TILE_UNITS = AW_THREADS * AW_UNROLL;  // 4-element units per tile
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+// Chunk arrays are device (global) memory: typed as such so that loads and stores are
+// global_* instructions instead of flat_* ones.
+typedef PT_GLOBAL f32x4* gf32x4_ptr;
+typedef PT_GLOBAL u32x2* gu32x2_ptr;
+typedef const PT_GLOBAL f32x4* cgf32x4_ptr;
+typedef const PT_GLOBAL u32x2* cgu32x2_ptr;
+
+template <class P>
+__device__ __forceinline__ auto ld_stream(P p) {
+#if PT_AW_NT
+  return __builtin_nontemporal_load(p);
+#else
+  return *p;
+#endif
+}
+template <class T, class P>
+__device__ __forceinline__ void st_stream(T v, P p) {
+#if PT_AW_NT
+  __builtin_nontemporal_store(v, p);
+#else
+  *p = v;
+#endif
+}
 
 // Derives the nine fp32 constants of this update from the fp64 hyper-parameters
 // and the step's device scalars (Adam bias correction with t = applied updates
@@ -117,8 +150,8 @@ k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_
     // full afterwards and its param16 array was never uploaded, so it is refilled from the
     // untouched master weights (param16 == RNE(master) is the invariant of every update).
     if (recast_on_skip) {
-      const f32x4* wq = reinterpret_cast<const f32x4*>(table[size_t(ROW_MASTER) * table_cols + first_col + blockIdx.y]);
-      u32x2* pq = reinterpret_cast<u32x2*>(table[size_t(ROW_P16) * table_cols + first_col + blockIdx.y]);
+      cgf32x4_ptr wq = (cgf32x4_ptr)(table[size_t(ROW_MASTER) * table_cols + first_col + blockIdx.y]);
+      gu32x2_ptr pq = (gu32x2_ptr)(table[size_t(ROW_P16) * table_cols + first_col + blockIdx.y]);
       const uint64_t n_units = S / 4;
       for (uint64_t u = uint64_t(blockIdx.x) * AW_THREADS + threadIdx.x; u < n_units;
            u += uint64_t(gridDim.x) * AW_THREADS) {
@@ -136,11 +169,11 @@ k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_
   k.step_size = st->c[5]; k.rsb2 = st->c[6]; k.eps = st->c[7]; k.gm = st->c[8];
 
   const uint32_t col = first_col + blockIdx.y;
-  const u32x2* __restrict__ gp = reinterpret_cast<const u32x2*>(table[size_t(ROW_GRAD) * table_cols + col]);
-  f32x4* __restrict__ wp = reinterpret_cast<f32x4*>(table[size_t(ROW_MASTER) * table_cols + col]);
-  f32x4* __restrict__ mp = reinterpret_cast<f32x4*>(table[size_t(ROW_M) * table_cols + col]);
-  f32x4* __restrict__ vp = reinterpret_cast<f32x4*>(table[size_t(ROW_V) * table_cols + col]);
-  u32x2* __restrict__ pp = reinterpret_cast<u32x2*>(table[size_t(ROW_P16) * table_cols + col]);
+  cgu32x2_ptr gp = (cgu32x2_ptr)(table[size_t(ROW_GRAD) * table_cols + col]);
+  gf32x4_ptr wp = (gf32x4_ptr)(table[size_t(ROW_MASTER) * table_cols + col]);
+  gf32x4_ptr mp = (gf32x4_ptr)(table[size_t(ROW_M) * table_cols + col]);
+  gf32x4_ptr vp = (gf32x4_ptr)(table[size_t(ROW_V) * table_cols + col]);
+  gu32x2_ptr pp = (gu32x2_ptr)(table[size_t(ROW_P16) * table_cols + col]);
 
   const uint64_t units = S / 4;
   const uint64_t full_tiles = units / AW_TILE_UNITS;
@@ -150,20 +183,20 @@ k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_
 #pragma unroll
     for (int r = 0; r < AW_UNROLL; ++r) {
       const uint64_t u = u0 + uint64_t(r) * AW_THREADS;
-      g[r] = __builtin_nontemporal_load(gp + u);
-      w[r] = __builtin_nontemporal_load(wp + u);
-      m[r] = __builtin_nontemporal_load(mp + u);
-      v[r] = __builtin_nontemporal_load(vp + u);
+      g[r] = ld_stream(gp + u);
+      w[r] = ld_stream(wp + u);
+      m[r] = ld_stream(mp + u);
+      v[r] = ld_stream(vp + u);
     }
 #pragma unroll
     for (int r = 0; r < AW_UNROLL; ++r) {
       const uint64_t u = u0 + uint64_t(r) * AW_THREADS;
       u32x2 p;
       update_unit<DT>(k, g[r], w[r], m[r], v[r], p);
-      __builtin_nontemporal_store(w[r], wp + u);
-      __builtin_nontemporal_store(m[r], mp + u);
-      __builtin_nontemporal_store(v[r], vp + u);
-      __builtin_nontemporal_store(p, pp + u);
+      st_stream(w[r], wp + u);
+      st_stream(m[r], mp + u);
+      st_stream(v[r], vp + u);
+      st_stream(p, pp + u);
     }
   }
   // ragged tail of the chunk (fewer than one tile of units), taken by block 0

@@ -13,6 +13,10 @@
 
 #include "ptchunk.h"
 
+// Device (global) address space qualifier for pointers rebuilt from integer addresses: the
+// compiler then emits global_* memory instructions instead of flat_* ones.
+#define PT_GLOBAL __attribute__((address_space(1)))
+
 // ---- device-resident scalars of a context ---------------------------------------
 // One instance per context, in device memory.  Written only by the single-thread
 // scalar kernels; read (uniformly) by the bulk kernels.

@@ -80,7 +80,7 @@ __global__ void __launch_bounds__(NB_THREADS)
 k_sqnorm(const uint64_t* __restrict__ grad_row, uint32_t first, uint64_t S,
          const PtDevState* __restrict__ st, double* __restrict__ part, uint32_t* __restrict__ flagout) {
   const uint32_t b = blockIdx.x, i = blockIdx.y;
-  const u32x4* base = reinterpret_cast<const u32x4*>(grad_row[first + i]);
+  const PT_GLOBAL u32x4* base = (const PT_GLOBAL u32x4*)(grad_row[first + i]);   // global_* loads
   const uint64_t vec_total = S / 8;
   const uint64_t v0 = uint64_t(b) * (PT_NORM_BLOCK_ELEMS / 8);
   uint64_t v1 = v0 + PT_NORM_BLOCK_ELEMS / 8;

@@ -51,7 +51,7 @@ __device__ __forceinline__ void accum_vec(const u32x4& q, double inv_scale, doub
   }
 }
 
-__device__ __forceinline__ u32x4 load_vec_unaligned16(const uint16_t* s) {
+__device__ __forceinline__ u32x4 load_vec_unaligned16(const PT_GLOBAL uint16_t* s) {
   // eight 16-bit loads: the source is only 2-byte aligned relative to the destination
   u32x4 q;
   q.x = uint32_t(s[0]) | (uint32_t(s[1]) << 16);
@@ -68,14 +68,15 @@ __global__ void __launch_bounds__(PK_THREADS)
 k_pack(const PtTile* __restrict__ tiles, const uint64_t* __restrict__ chunk_row,
        const PtDevState* __restrict__ st, double* __restrict__ tile_sq, uint32_t* __restrict__ tile_flag) {
   const PtTile t = tiles[blockIdx.x];
-  uint16_t* chunk_side = reinterpret_cast<uint16_t*>(chunk_row[t.chunk]) + t.chunk_off;
-  uint16_t* tensor_side = reinterpret_cast<uint16_t*>(t.tensor_addr);
-  const uint16_t* src = DIR == 0 ? tensor_side : chunk_side;
-  uint16_t* dst = DIR == 0 ? chunk_side : tensor_side;
+  // both sides are device (global) memory: typed so, to get global_* instead of flat_* accesses
+  PT_GLOBAL uint16_t* chunk_side = (PT_GLOBAL uint16_t*)(chunk_row[t.chunk]) + t.chunk_off;
+  PT_GLOBAL uint16_t* tensor_side = (PT_GLOBAL uint16_t*)(t.tensor_addr);
+  const PT_GLOBAL uint16_t* src = DIR == 0 ? tensor_side : chunk_side;
+  PT_GLOBAL uint16_t* dst = DIR == 0 ? chunk_side : tensor_side;
   const uint32_t len = t.len;
 
   // elements before the destination reaches a 16-byte boundary
-  uint32_t head = uint32_t(((16u - (uint32_t(reinterpret_cast<uintptr_t>(dst)) & 15u)) & 15u) >> 1);
+  uint32_t head = uint32_t(((16u - (uint32_t((uintptr_t)dst) & 15u)) & 15u) >> 1);
   if (head > len) head = len;
   const uint32_t nvec = (len - head) / 8;
   const uint32_t tail0 = head + nvec * 8;
@@ -97,10 +98,10 @@ k_pack(const PtTile* __restrict__ tiles, const uint64_t* __restrict__ chunk_row,
     if (DIR == 0) { a1 += word_sq<DT>(w, inv_scale); flag |= word_nonfinite<DT>(w); }
   }
 
-  const uint16_t* sb = src + head;
-  u32x4* db = reinterpret_cast<u32x4*>(dst + head);
-  if ((reinterpret_cast<uintptr_t>(sb) & 15u) == 0) {
-    const u32x4* sv = reinterpret_cast<const u32x4*>(sb);
+  const PT_GLOBAL uint16_t* sb = src + head;
+  PT_GLOBAL u32x4* db = (PT_GLOBAL u32x4*)(dst + head);
+  if (((uintptr_t)sb & 15u) == 0) {
+    const PT_GLOBAL u32x4* sv = (const PT_GLOBAL u32x4*)sb;
     uint32_t i = threadIdx.x;
     for (; i + 3 * PK_THREADS < nvec; i += 4 * PK_THREADS) {
       u32x4 q0 = __builtin_nontemporal_load(sv + i);

@@ -65,15 +65,20 @@ int main(int argc, char** argv) {
     memcpy(&hw[i], &b, 4);
   }
 
+  // PROBE_SKEW=<bytes> (multiple of 16): array k of a chunk starts k*skew bytes into its
+  // allocation, to see how the relative placement of the five arrays matters
+  const size_t skew = getenv("PROBE_SKEW") ? strtoull(getenv("PROBE_SKEW"), nullptr, 10) & ~size_t(15) : 0;
+  const size_t extra = 6 * skew;
   std::vector<void*> src(C), g(C), p(C);
   std::vector<float*> w(C), m(C), v(C);
   for (uint32_t c = 0; c < C; ++c) {
-    CHECK_HIP(hipMalloc(&src[c], 2 * S));
-    CHECK_HIP(hipMalloc(&g[c], 2 * S));
-    CHECK_HIP(hipMalloc(&p[c], 2 * S));
-    CHECK_HIP(hipMalloc((void**)&w[c], 4 * S));
-    CHECK_HIP(hipMalloc((void**)&m[c], 4 * S));
-    CHECK_HIP(hipMalloc((void**)&v[c], 4 * S));
+    char* q;
+    CHECK_HIP(hipMalloc((void**)&q, 2 * S + extra)); src[c] = q;
+    CHECK_HIP(hipMalloc((void**)&q, 2 * S + extra)); g[c] = q + 1 * skew;
+    CHECK_HIP(hipMalloc((void**)&q, 2 * S + extra)); p[c] = q + 2 * skew;
+    CHECK_HIP(hipMalloc((void**)&q, 4 * S + extra)); w[c] = (float*)(q + 3 * skew);
+    CHECK_HIP(hipMalloc((void**)&q, 4 * S + extra)); m[c] = (float*)(q + 4 * skew);
+    CHECK_HIP(hipMalloc((void**)&q, 4 * S + extra)); v[c] = (float*)(q + 5 * skew);
     CHECK_HIP(hipMemcpy(src[c], hg.data(), 2 * S, hipMemcpyHostToDevice));
     CHECK_HIP(hipMemcpy(p[c], hp.data(), 2 * S, hipMemcpyHostToDevice));
     CHECK_HIP(hipMemcpy(w[c], hw.data(), 4 * S, hipMemcpyHostToDevice));
