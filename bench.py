@@ -31,6 +31,8 @@ PACK_BYTES_PER_ELEM = 4            # read 2 + write 2
 # HBM traffic of one AdamW launch from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by the
 # same counters on pt_calib_copy); filled from the summaries under profiles/.  bytes per launch.
 MEASURED_TRAFFIC = {
+    # profiles/k_adamw_llama7b_hbm_traffic.md: (46 334 987.97 x 1.99978 + 92 671 995.88 x 0.99998) KiB
+    "llama_7b": 189_778_112_000,
 }
 
 
