@@ -40,6 +40,165 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def run_streamed(args) -> int:
+    """LLaMA-13B-shaped state: chunks [0, C/2) resident in HBM, chunks [C/2, C/2 + n_host) in pinned
+    host memory.  Timed step = pack (resident) -> finalize -> pt_chunk_stream_step (host chunks,
+    side streams) -> pt_chunk_adamw_step (resident, overlapped) -> pt_step_end (join).  The host
+    chunks' gradients were packed and reduced on the GPU and offloaded in the untimed set-up."""
+    import numpy as np
+    import torch
+
+    from paper_2406_08334_amd import binding as B
+    from paper_2406_08334_amd import shapes, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    B.lib()
+    table, S = shapes.workload("llama_13b")
+    sizes = [n for _, n in table]
+    N = sum(sizes)
+    segs, C = B.pt_layout_dense(sizes, S)
+    n_persist = C // 2
+    n_host = C - n_persist if args.host_chunks <= 0 else min(args.host_chunks, C - n_persist)
+    log(f"[bench] llama_13b: {C} chunks of {S:,}; {n_persist} resident ({16 * n_persist * S / 1e9:.1f} GB HBM), "
+        f"{n_host} in pinned host memory ({16 * n_host * S / 1e9:.1f} GB), {args.slots} chunk buffers")
+    t0 = time.time()
+    ctx = B.pt_ctx_create(B.PT_BF16, S, C, None)
+    B.pt_stream_reserve(ctx, args.slots)
+    n_res = n_persist * S
+    g16 = torch.zeros(n_persist, S, dtype=torch.bfloat16, device=dev)
+    p16 = torch.zeros(n_persist, S, dtype=torch.bfloat16, device=dev)
+    synth.normal_16(synth.SEED_PARAMS, 0, 0, 0, n_res, 0.02, torch.bfloat16, dev, out=p16.view(-1))
+    w = torch.empty(n_persist, S, dtype=torch.float32, device=dev)
+    for c in range(n_persist):
+        w[c].copy_(p16[c])
+    m = torch.zeros(n_persist, S, dtype=torch.float32, device=dev)
+    v = torch.zeros(n_persist, S, dtype=torch.float32, device=dev)
+    grad_src = torch.empty(n_res, dtype=torch.bfloat16, device=dev)
+    synth.normal_16(synth.SEED_GRADS, 1, 0, 0, n_res, 1e-3, torch.bfloat16, dev, out=grad_src)
+    offs = np.cumsum([0] + sizes[:-1]).tolist()
+    res_segs = [s for s in segs if s.chunk < n_persist]
+    for s in res_segs:
+        s.src = grad_src.data_ptr() + 2 * offs[s.tensor]
+    plan = B.pt_pack_plan_create(ctx, res_segs)
+    # host chunks: generated on the GPU, reduced there, then offloaded (untimed)
+    pin = lambda dt: torch.empty(S, dtype=dt).pin_memory()
+    h_g, h_p, h_w, h_m, h_v = [], [], [], [], []
+    tmp16 = torch.empty(S, dtype=torch.bfloat16, device=dev)
+    tmp32 = torch.empty(S, dtype=torch.float32, device=dev)
+    n_want = n_host
+    for i in range(n_host):
+        c = n_persist + i
+        real = max(0, min(S, N - c * S))
+        try:
+            bufs = [pin(torch.bfloat16), pin(torch.bfloat16), pin(torch.float32), pin(torch.float32), pin(torch.float32)]
+        except RuntimeError as e:       # the box pins only so much host memory: run with what fits
+            if "out of memory" not in str(e):
+                raise
+            n_host = max(0, i - 1)      # keep one chunk of headroom
+            for lst in (h_g, h_p, h_w, h_m, h_v):
+                del lst[n_host:]
+            log(f"[bench] pinned host memory exhausted after {i} chunks ({16 * i * S / 1e9:.1f} GB): "
+                f"streaming {n_host} host chunks instead of {n_want}")
+            break
+        tmp16.zero_()
+        if real:
+            synth.normal_16(synth.SEED_GRADS, 1, 0, c * S, real, 1e-3, torch.bfloat16, dev, out=tmp16[:real])
+        ptrs = [None] * C
+        ptrs[c] = tmp16
+        B.pt_chunk_grad_sqnorm(ctx, ptrs, c, 1, False)
+        h_g.append(bufs[0]); h_g[-1].copy_(tmp16)
+        tmp16.zero_()
+        if real:
+            synth.normal_16(synth.SEED_PARAMS, 0, 0, c * S, real, 0.02, torch.bfloat16, dev, out=tmp16[:real])
+        h_p.append(bufs[1]); h_p[-1].copy_(tmp16)
+        tmp32.copy_(tmp16)
+        h_w.append(bufs[2]); h_w[-1].copy_(tmp32)
+        h_m.append(bufs[3]); h_m[-1].zero_()
+        h_v.append(bufs[4]); h_v[-1].zero_()
+        if i % 16 == 0:
+            log(f"[bench] host chunk {i}/{n_want} ready ({time.time() - t0:.0f} s)")
+    assert n_host >= 2, "could not pin even two host chunks"
+    torch.cuda.synchronize()
+    log(f"[bench] state generated in {time.time() - t0:.1f} s")
+
+    # ---- bare link rate with the same pinned buffers: one direction at a time, then both at once
+    stream = torch.cuda.current_stream()
+    s_a, s_b = torch.cuda.Stream(), torch.cuda.Stream()
+    dst_up, src_dn = torch.empty(S, dtype=torch.float32, device=dev), torch.empty(S, dtype=torch.float32, device=dev)
+    n_cal = min(8, n_host)
+
+    def link(up, down):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(n_cal):
+            if up:
+                with torch.cuda.stream(s_a):
+                    dst_up.copy_(h_w[i], non_blocking=True)
+            if down:
+                with torch.cuda.stream(s_b):
+                    h_v[i].copy_(src_dn, non_blocking=True)
+        torch.cuda.synchronize()
+        return 4 * S * n_cal / (time.perf_counter() - t) / 1e9
+    src_dn.zero_()
+    link(True, True)
+    bare = {"h2d_alone": round(link(True, False), 2), "d2h_alone": round(link(False, True), 2),
+            "each_direction_when_both": round(link(True, True), 2)}
+    log(f"[bench] bare pinned copies, GB/s: {bare}")
+
+    hp = B.hparams(**HP)
+    rows = lambda a: [a[c] for c in range(n_persist)]
+    r_g, r_w, r_m, r_v, r_p = rows(g16), rows(w), rows(m), rows(v), rows(p16)
+    pack_rows = r_g + [None] * (C - n_persist)
+
+    def one_step(streamed=True, resident=True):
+        B.pt_chunk_pack_grads(ctx, plan, pack_rows, stream)
+        B.pt_chunk_grad_sqnorm(ctx, None, 0, C, True, stream)
+        if streamed:
+            B.pt_chunk_stream_step(ctx, hp, n_persist, n_host, h_g, h_w, h_m, h_v, h_p, stream)
+        if resident:
+            B.pt_chunk_adamw_step(ctx, hp, 0, n_persist, r_g, r_w, r_m, r_v, r_p, stream)
+        B.pt_step_end(ctx, stream)
+
+    def timed(k, **kw):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(k):
+            one_step(**kw)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / k
+
+    for _ in range(args.warmup):
+        one_step()
+    K = args.steps
+    t_step = timed(K)
+    t_res = timed(max(K, 3), streamed=False)
+    t_str = timed(K, resident=False)
+    rep = B.pt_step_report_read(ctx, stream)
+    link_bytes = 14 * S * n_host
+    per_dir = link_bytes / t_step / 1e9
+    ref = bare["each_direction_when_both"]
+    out = {
+        "metric": "streamed chunked AdamW step: host-link GB/s per direction (both directions busy) + ms/step",
+        "value": round(per_dir, 2), "unit": "GB/s per direction", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": round(1e3 * t_step, 2), "higher_is_better": True, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"llama_13b: {C} chunks of {S}; chunks [0,{n_persist}) resident, "
+                               f"[{n_persist},{n_persist + n_host}) in pinned host memory, {args.slots} chunk buffers",
+                   "n_persist": n_persist, "n_host": n_host, "n_host_wanted": n_want, "slots": args.slots,
+                   "link_bytes_per_direction": link_bytes},
+        "bare_link_GBps": bare,
+        "link_utilisation_vs_bare_bidirectional": round(per_dir / ref, 4),
+        "ms_resident_only": round(1e3 * t_res, 2), "ms_streamed_only": round(1e3 * t_str, 2),
+        "overlap_ratio_step_over_max": round(t_step / max(t_res, t_str), 4),
+        "step_report": {"norm": rep.norm, "found_inf": rep.found_inf, "step": rep.step},
+    }
+    B.pt_pack_plan_destroy(plan)
+    B.pt_ctx_destroy(ctx)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -50,11 +209,18 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-chunks", type=int, default=4)
     ap.add_argument("--calib", action="store_true", help="also time a bare copy kernel (attainable HBM rate)")
+    ap.add_argument("--stream", action="store_true",
+                    help="the streamed configuration instead: LLaMA-13B shape, first half of the chunks resident, "
+                         "the rest in pinned host memory through pt_chunk_stream_step")
+    ap.add_argument("--host-chunks", type=int, default=0, help="--stream: host-resident chunks (default: all of the second half)")
+    ap.add_argument("--slots", type=int, default=3, help="--stream: device chunk buffers")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
               "run it with --gpus 1. How the path would shard is described in DESIGN.md.", file=sys.stderr)
         return 2
+    if args.stream:
+        return run_streamed(args)
 
     import numpy as np
     import torch
