@@ -125,6 +125,13 @@ int pt_ctx_destroy(pt_ctx* ctx);
 /* Overwrites the step counter / loss-scale state (resume).  Enqueued on stream. */
 int pt_ctx_set_state(pt_ctx* ctx, int32_t step, double loss_scale, int32_t good_steps, void* stream);
 
+/* Launch-shape options (host state only, take effect at the next call; none of them
+ * changes a result bit).
+ *   "adamw_grid"    workgroups of the update kernel; 0 = the library's default
+ *   "adamw_unroll"  4-element units a lane loads before it computes: 1, 2, 4 or 8
+ *   "adamw_nt"      1 = non-temporal hints on the update's loads and stores (default), 0 = none */
+int pt_ctx_set_option(pt_ctx* ctx, const char* name, int64_t value);
+
 /* ---- layout (host, integer only) ---------------------------------------------------
  * Dense layout: the tensors are concatenated in the order given and cut every
  * chunk_elems elements; a tensor may straddle a chunk boundary; only the tail of

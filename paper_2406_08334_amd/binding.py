@@ -20,7 +20,7 @@ EXPORTS = [
     "pt_version", "pt_status_string", "pt_last_error", "pt_ctx_create", "pt_ctx_destroy", "pt_ctx_set_state",
     "pt_layout_dense", "pt_pack_plan_create", "pt_pack_plan_destroy", "pt_chunk_pack_grads", "pt_chunk_unpack",
     "pt_chunk_grad_sqnorm", "pt_chunk_adamw_step", "pt_stream_reserve", "pt_chunk_stream_step", "pt_step_end",
-    "pt_step_report_read", "pt_update_consts_read", "pt_step_override", "pt_calib_copy",
+    "pt_step_report_read", "pt_update_consts_read", "pt_step_override", "pt_calib_copy", "pt_ctx_set_option",
 ]
 
 
@@ -96,6 +96,7 @@ def lib():
         L.pt_update_consts_read.argtypes = [vp, C.POINTER(pt_update_consts), vp]
         L.pt_step_override.argtypes = [vp, C.c_float, i32, vp]
         L.pt_calib_copy.argtypes = [vp, vp, u64, vp]
+        L.pt_ctx_set_option.argtypes = [vp, C.c_char_p, C.c_int64]
         for name in EXPORTS:
             if name not in ("pt_version", "pt_status_string", "pt_last_error"):
                 getattr(L, name).restype = C.c_int
@@ -256,3 +257,7 @@ def pt_step_override(ctx, grad_mult: float, found_inf: bool, stream=None):
 
 def pt_calib_copy(dst, src, nbytes: int, stream=None):
     _check(lib().pt_calib_copy(_addr(dst), _addr(src), int(nbytes), _stream(stream)), "pt_calib_copy")
+
+
+def pt_ctx_set_option(ctx, name: str, value: int):
+    _check(lib().pt_ctx_set_option(ctx, name.encode(), int(value)), "pt_ctx_set_option", ctx)

@@ -16,19 +16,7 @@
 
 namespace {
 
-#ifndef PT_AW_THREADS
-#define PT_AW_THREADS 256
-#endif
-#ifndef PT_AW_UNROLL
-#define PT_AW_UNROLL 4
-#endif
-#ifndef PT_AW_NT
-#define PT_AW_NT 1        // non-temporal hints: every byte is touched once per step
-#endif
-
-constexpr int AW_THREADS = PT_AW_THREADS;
-constexpr int AW_UNROLL = PT_AW_UNROLL;
-constexpr uint32_t AW_TILE_UNITS = AW_THREADS * AW_UNROLL;  // 4-element units per tile
+constexpr int AW_THREADS = 256;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -39,21 +27,16 @@ typedef PT_GLOBAL u32x2* gu32x2_ptr;
 typedef const PT_GLOBAL f32x4* cgf32x4_ptr;
 typedef const PT_GLOBAL u32x2* cgu32x2_ptr;
 
-template <class P>
+// NT: non-temporal hints (every byte is touched once per step).
+template <bool NT, class P>
 __device__ __forceinline__ auto ld_stream(P p) {
-#if PT_AW_NT
-  return __builtin_nontemporal_load(p);
-#else
-  return *p;
-#endif
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
 }
-template <class T, class P>
+template <bool NT, class T, class P>
 __device__ __forceinline__ void st_stream(T v, P p) {
-#if PT_AW_NT
-  __builtin_nontemporal_store(v, p);
-#else
-  *p = v;
-#endif
+  if constexpr (NT) __builtin_nontemporal_store(v, p);
+  else *p = v;
 }
 
 // Derives the nine fp32 constants of this update from the fp64 hyper-parameters
@@ -139,27 +122,34 @@ __device__ __forceinline__ void update_unit(const Consts& k, u32x2 g2, f32x4& w,
   p2.y = pw[2] | (pw[3] << 16);
 }
 
-// grid = (blocks_per_chunk, n_cols).  Block (bx, i) walks the tiles
-// bx, bx+gridDim.x, ... of the chunk in table column first_col+i.
-template <int DT>
+// One flat index space of tiles (256 x UNROLL units of 4 elements) over all chunks of
+// the launch: tile T belongs to chunk T / tiles_per_chunk.  Block b takes tiles
+// b, b + gridDim.x, ...  A block's consecutive tiles mostly stay in one chunk, so the
+// five base pointers are re-read from the table only when the chunk changes.
+template <int DT, int UNROLL, bool NT>
 __global__ void __launch_bounds__(AW_THREADS)
-k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_col, uint64_t S,
-        const PtDevState* __restrict__ st, int recast_on_skip) {
+k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_col, uint32_t n_cols,
+        uint64_t S, uint32_t tiles_per_chunk, const PtDevState* __restrict__ st, int recast_on_skip) {
+  constexpr uint32_t TILE_UNITS = AW_THREADS * UNROLL;
+  const uint64_t units = S / 4;
+  const uint32_t total_tiles = tiles_per_chunk * n_cols;
   if (st->skip) {
     // Skipped step: nothing changes.  A chunk buffer of the streamed path is offloaded in
     // full afterwards and its param16 array was never uploaded, so it is refilled from the
     // untouched master weights (param16 == RNE(master) is the invariant of every update).
     if (recast_on_skip) {
-      cgf32x4_ptr wq = (cgf32x4_ptr)(table[size_t(ROW_MASTER) * table_cols + first_col + blockIdx.y]);
-      gu32x2_ptr pq = (gu32x2_ptr)(table[size_t(ROW_P16) * table_cols + first_col + blockIdx.y]);
-      const uint64_t n_units = S / 4;
-      for (uint64_t u = uint64_t(blockIdx.x) * AW_THREADS + threadIdx.x; u < n_units;
-           u += uint64_t(gridDim.x) * AW_THREADS) {
-        f32x4 w = wq[u];
-        u32x2 p;
-        p.x = encode16<DT>(w[0]) | (encode16<DT>(w[1]) << 16);
-        p.y = encode16<DT>(w[2]) | (encode16<DT>(w[3]) << 16);
-        pq[u] = p;
+      for (uint32_t T = blockIdx.x; T < total_tiles; T += gridDim.x) {
+        const uint32_t ci = T / tiles_per_chunk, tile = T - ci * tiles_per_chunk;
+        cgf32x4_ptr wq = (cgf32x4_ptr)(table[size_t(ROW_MASTER) * table_cols + first_col + ci]);
+        gu32x2_ptr pq = (gu32x2_ptr)(table[size_t(ROW_P16) * table_cols + first_col + ci]);
+        const uint64_t u_end = min(units, (uint64_t(tile) + 1) * TILE_UNITS);
+        for (uint64_t u = uint64_t(tile) * TILE_UNITS + threadIdx.x; u < u_end; u += AW_THREADS) {
+          f32x4 w = wq[u];
+          u32x2 p;
+          p.x = encode16<DT>(w[0]) | (encode16<DT>(w[1]) << 16);
+          p.y = encode16<DT>(w[2]) | (encode16<DT>(w[3]) << 16);
+          pq[u] = p;
+        }
       }
     }
     return;
@@ -168,44 +158,63 @@ k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_
   k.b1 = st->c[0]; k.b2 = st->c[1]; k.omb1 = st->c[2]; k.omb2 = st->c[3]; k.decay = st->c[4];
   k.step_size = st->c[5]; k.rsb2 = st->c[6]; k.eps = st->c[7]; k.gm = st->c[8];
 
-  const uint32_t col = first_col + blockIdx.y;
-  cgu32x2_ptr gp = (cgu32x2_ptr)(table[size_t(ROW_GRAD) * table_cols + col]);
-  gf32x4_ptr wp = (gf32x4_ptr)(table[size_t(ROW_MASTER) * table_cols + col]);
-  gf32x4_ptr mp = (gf32x4_ptr)(table[size_t(ROW_M) * table_cols + col]);
-  gf32x4_ptr vp = (gf32x4_ptr)(table[size_t(ROW_V) * table_cols + col]);
-  gu32x2_ptr pp = (gu32x2_ptr)(table[size_t(ROW_P16) * table_cols + col]);
-
-  const uint64_t units = S / 4;
-  const uint64_t full_tiles = units / AW_TILE_UNITS;
-  for (uint64_t tile = blockIdx.x; tile < full_tiles; tile += gridDim.x) {
-    const uint64_t u0 = tile * AW_TILE_UNITS + threadIdx.x;
-    u32x2 g[AW_UNROLL]; f32x4 w[AW_UNROLL], m[AW_UNROLL], v[AW_UNROLL];
-#pragma unroll
-    for (int r = 0; r < AW_UNROLL; ++r) {
-      const uint64_t u = u0 + uint64_t(r) * AW_THREADS;
-      g[r] = ld_stream(gp + u);
-      w[r] = ld_stream(wp + u);
-      m[r] = ld_stream(mp + u);
-      v[r] = ld_stream(vp + u);
+  uint32_t cur = 0xffffffffu;
+  cgu32x2_ptr gp = nullptr;
+  gf32x4_ptr wp = nullptr, mp = nullptr, vp = nullptr;
+  gu32x2_ptr pp = nullptr;
+  for (uint32_t T = blockIdx.x; T < total_tiles; T += gridDim.x) {
+    const uint32_t ci = T / tiles_per_chunk, tile = T - ci * tiles_per_chunk;
+    if (ci != cur) {
+      cur = ci;
+      const uint32_t col = first_col + ci;
+      gp = (cgu32x2_ptr)(table[size_t(ROW_GRAD) * table_cols + col]);
+      wp = (gf32x4_ptr)(table[size_t(ROW_MASTER) * table_cols + col]);
+      mp = (gf32x4_ptr)(table[size_t(ROW_M) * table_cols + col]);
+      vp = (gf32x4_ptr)(table[size_t(ROW_V) * table_cols + col]);
+      pp = (gu32x2_ptr)(table[size_t(ROW_P16) * table_cols + col]);
     }
+    const uint64_t u0 = uint64_t(tile) * TILE_UNITS + threadIdx.x;
+    if ((uint64_t(tile) + 1) * TILE_UNITS <= units) {
+      u32x2 g[UNROLL]; f32x4 w[UNROLL], m[UNROLL], v[UNROLL];
 #pragma unroll
-    for (int r = 0; r < AW_UNROLL; ++r) {
-      const uint64_t u = u0 + uint64_t(r) * AW_THREADS;
-      u32x2 p;
-      update_unit<DT>(k, g[r], w[r], m[r], v[r], p);
-      st_stream(w[r], wp + u);
-      st_stream(m[r], mp + u);
-      st_stream(v[r], vp + u);
-      st_stream(p, pp + u);
+      for (int r = 0; r < UNROLL; ++r) {
+        const uint64_t u = u0 + uint64_t(r) * AW_THREADS;
+        g[r] = ld_stream<NT>(gp + u);
+        w[r] = ld_stream<NT>(wp + u);
+        m[r] = ld_stream<NT>(mp + u);
+        v[r] = ld_stream<NT>(vp + u);
+      }
+#pragma unroll
+      for (int r = 0; r < UNROLL; ++r) {
+        const uint64_t u = u0 + uint64_t(r) * AW_THREADS;
+        u32x2 p;
+        update_unit<DT>(k, g[r], w[r], m[r], v[r], p);
+        st_stream<NT>(w[r], wp + u);
+        st_stream<NT>(m[r], mp + u);
+        st_stream<NT>(v[r], vp + u);
+        st_stream<NT>(p, pp + u);
+      }
+    } else {
+      // ragged last tile of a chunk
+      for (uint64_t u = u0; u < units; u += AW_THREADS) {
+        u32x2 g = gp[u]; f32x4 w = wp[u], m = mp[u], v = vp[u]; u32x2 p;
+        update_unit<DT>(k, g, w, m, v, p);
+        wp[u] = w; mp[u] = m; vp[u] = v; pp[u] = p;
+      }
     }
   }
-  // ragged tail of the chunk (fewer than one tile of units), taken by block 0
-  if (blockIdx.x == 0) {
-    for (uint64_t u = full_tiles * AW_TILE_UNITS + threadIdx.x; u < units; u += AW_THREADS) {
-      u32x2 g = gp[u]; f32x4 w = wp[u], m = mp[u], v = vp[u]; u32x2 p;
-      update_unit<DT>(k, g, w, m, v, p);
-      wp[u] = w; mp[u] = m; vp[u] = v; pp[u] = p;
-    }
+}
+
+typedef void (*adamw_kernel_t)(const uint64_t*, uint32_t, uint32_t, uint32_t, uint64_t, uint32_t,
+                               const PtDevState*, int);
+
+template <int DT>
+adamw_kernel_t pick_kernel(uint32_t unroll, bool nt) {
+  switch (unroll) {
+    case 1: return nt ? k_adamw<DT, 1, true> : k_adamw<DT, 1, false>;
+    case 2: return nt ? k_adamw<DT, 2, true> : k_adamw<DT, 2, false>;
+    case 8: return nt ? k_adamw<DT, 8, true> : k_adamw<DT, 8, false>;
+    default: return nt ? k_adamw<DT, 4, true> : k_adamw<DT, 4, false>;
   }
 }
 
@@ -224,39 +233,24 @@ int pt_prepare_consts(pt_ctx* ctx, const pt_hparams* hp, hipStream_t stream) {
   return PT_OK;
 }
 
-// Blocks per chunk: enough tiles per block to amortise the launch of a block,
-// enough blocks to fill 256 CUs many times over.
-static uint32_t adamw_blocks_per_chunk(const pt_ctx* ctx, uint32_t n_cols) {
-  uint64_t tiles = (ctx->S / 4) / AW_TILE_UNITS;
-  if (tiles == 0) return 1;
-  static int env_bpc = -1;
-  if (env_bpc < 0) {
-    const char* e = getenv("PTCHUNK_ADAMW_BLOCKS_PER_CHUNK");
-    env_bpc = e ? atoi(e) : 0;
-  }
-  uint64_t want;
-  if (env_bpc > 0) {
-    want = (uint64_t)env_bpc;
-  } else {
-    // aim at about 16 resident blocks per CU over the whole launch
-    uint64_t target_total = 256ull * 16ull;
-    want = (target_total + n_cols - 1) / n_cols;
-    if (want < 8) want = 8;
-  }
-  if (want > tiles) want = tiles;
-  if (want > 0x7fffffffull) want = 0x7fffffffull;
-  return (uint32_t)want;
-}
-
 int pt_launch_adamw(pt_ctx* ctx, uint32_t first_col, uint32_t n_cols, hipStream_t stream, bool recast_on_skip) {
   if (n_cols == 0) return PT_OK;
-  dim3 grid(adamw_blocks_per_chunk(ctx, n_cols), n_cols);
-  if (ctx->dtype == PT_BF16)
-    hipLaunchKernelGGL(k_adamw<PT_BF16>, grid, dim3(AW_THREADS), 0, stream, ctx->d_table, ctx->table_cols,
-                       first_col, ctx->S, ctx->d_state, recast_on_skip ? 1 : 0);
-  else
-    hipLaunchKernelGGL(k_adamw<PT_FP16>, grid, dim3(AW_THREADS), 0, stream, ctx->d_table, ctx->table_cols,
-                       first_col, ctx->S, ctx->d_state, recast_on_skip ? 1 : 0);
+  const uint32_t unroll = ctx->opt_adamw_unroll;
+  const uint64_t units = ctx->S / 4;
+  const uint64_t tile_units = uint64_t(AW_THREADS) * unroll;
+  const uint64_t tpc = (units + tile_units - 1) / tile_units;
+  if (tpc * n_cols > 0x7fffffffull)
+    return pt_fail(ctx, PT_ERR_UNSUPPORTED, "update launch of %u chunks exceeds 2^31 tiles", n_cols);
+  const uint32_t total = uint32_t(tpc) * n_cols;
+  // Grid: measured on MI355X, many short-lived workgroups (about three tiles each) keep the
+  // memory system a few percent busier than a grid sized to what stays resident.
+  uint32_t want = ctx->opt_adamw_grid > 0 ? ctx->opt_adamw_grid : (total + 2) / 3;
+  if (ctx->opt_adamw_grid == 0 && want < PT_ADAMW_MIN_GRID) want = PT_ADAMW_MIN_GRID;
+  dim3 grid(want < total ? want : total);
+  adamw_kernel_t kern = ctx->dtype == PT_BF16 ? pick_kernel<PT_BF16>(unroll, ctx->opt_adamw_nt != 0)
+                                              : pick_kernel<PT_FP16>(unroll, ctx->opt_adamw_nt != 0);
+  hipLaunchKernelGGL(kern, grid, dim3(AW_THREADS), 0, stream, ctx->d_table, ctx->table_cols, first_col, n_cols,
+                     ctx->S, uint32_t(tpc), ctx->d_state, recast_on_skip ? 1 : 0);
   PT_LAUNCH_CHECK(ctx, "k_adamw");
   return PT_OK;
 }

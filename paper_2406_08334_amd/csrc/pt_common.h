@@ -54,6 +54,8 @@ enum PtRow : int {
 };
 
 constexpr uint32_t PT_MAX_SLOTS = 8;
+constexpr uint32_t PT_ADAMW_MIN_GRID = 16384;      // default grid of the update kernel: max(this, tiles / 3)
+constexpr uint32_t PT_ADAMW_DEFAULT_UNROLL = 4;
 constexpr uint32_t PT_NORM_BLOCK_ELEMS = 32768;  // elements one block of the norm kernel reduces
 constexpr uint32_t PT_PACK_TILE_ELEMS = 16384;   // chunk-space tile of the pack kernel
 
@@ -82,6 +84,10 @@ struct pt_ctx {
   uint32_t C = 0;          // n_chunks
   uint32_t norm_blocks = 0;  // blocks per chunk of the norm kernel
   uint32_t table_cols = 0;   // C + PT_MAX_SLOTS
+  // launch-shape options (pt_ctx_set_option)
+  uint32_t opt_adamw_grid = 0;      // workgroups of the update kernel; 0 = max(PT_ADAMW_MIN_GRID, tiles / 3)
+  uint32_t opt_adamw_unroll = PT_ADAMW_DEFAULT_UNROLL;  // 4-element units per lane per tile: 1, 2, 4 or 8
+  uint32_t opt_adamw_nt = 1;        // non-temporal hints on the update's loads and stores
   bool scaler = false;
 
   PtDevState* d_state = nullptr;

@@ -2,6 +2,8 @@
 // single-thread scalar kernels (state set / override / step end).
 #include "pt_common.h"
 
+#include <cstdlib>
+
 static thread_local std::string g_noctx_error;
 
 int pt_fail(pt_ctx* ctx, int status, const char* fmt, ...) {
@@ -186,6 +188,27 @@ extern "C" int pt_ctx_set_state(pt_ctx* ctx, int32_t step, double loss_scale, in
   return PT_OK;
 }
 
+extern "C" int pt_ctx_set_option(pt_ctx* ctx, const char* name, int64_t value) {
+  if (!ctx) return PT_ERR_INVALID_ARG;
+  if (!name) return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_ctx_set_option: name is NULL");
+  if (std::strcmp(name, "adamw_grid") == 0) {
+    if (value < 0 || value > (1 << 20)) return pt_fail(ctx, PT_ERR_INVALID_ARG, "adamw_grid must be in [0, 2^20]");
+    ctx->opt_adamw_grid = uint32_t(value);
+    return PT_OK;
+  }
+  if (std::strcmp(name, "adamw_unroll") == 0) {
+    if (value != 1 && value != 2 && value != 4 && value != 8)
+      return pt_fail(ctx, PT_ERR_INVALID_ARG, "adamw_unroll must be 1, 2, 4 or 8");
+    ctx->opt_adamw_unroll = uint32_t(value);
+    return PT_OK;
+  }
+  if (std::strcmp(name, "adamw_nt") == 0) {
+    ctx->opt_adamw_nt = value != 0;
+    return PT_OK;
+  }
+  return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_ctx_set_option: unknown option '%s'", name);
+}
+
 extern "C" int pt_step_override(pt_ctx* ctx, float grad_mult, int32_t found_inf, void* stream) {
   if (!ctx) return PT_ERR_INVALID_ARG;
   hipLaunchKernelGGL(k_override, dim3(1), dim3(1), 0, (hipStream_t)stream, ctx->d_state, grad_mult,
@@ -313,6 +336,10 @@ extern "C" int pt_calib_copy(void* dst, const void* src, uint64_t bytes, void* s
   uint64_t n_vec = bytes / 16;
   uint64_t blocks = (n_vec + 1023) / 1024;
   if (blocks > 256 * 32) blocks = 256 * 32;
+  if (const char* e = getenv("PTCHUNK_COPY_BLOCKS")) {        // calibration experiments only
+    uint64_t b = strtoull(e, nullptr, 10);
+    if (b > 0 && b <= (1u << 24)) blocks = b;
+  }
   hipLaunchKernelGGL(k_calib_copy, dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream,
                      (u32x4_t*)dst, (const u32x4_t*)src, n_vec);
   if (hipGetLastError() != hipSuccess) return pt_fail(nullptr, PT_ERR_HIP, "pt_calib_copy: launch failed");

@@ -118,6 +118,40 @@ int main(int argc, char** argv) {
     printf("step %d: pack %.3f ms (%.0f GB/s)  finalize %.3f ms  adamw %.3f ms (%.0f GB/s)  norm %.6f step %d\n", s,
            t_pack, 4.0 * n / t_pack / 1e6, t_norm, t_adamw, 28.0 * n / t_adamw / 1e6, rep.norm, rep.step);
   }
+  // PROBE_GRIDS="4096,16384,..." [PROBE_UNROLLS="4,8"] [PROBE_NT="1,0"]: times the update alone for
+  // every combination, in this one process on these allocations (placement differs run to run)
+  if (const char* gl = getenv("PROBE_GRIDS")) {
+    auto parse = [](const char* q, std::vector<long>& out) {
+      while (q && *q) { char* end; out.push_back(strtol(q, &end, 10)); q = (*end == ',') ? end + 1 : end; if (end == q && *q) break; }
+    };
+    std::vector<long> grids, unrolls, nts;
+    parse(gl, grids);
+    parse(getenv("PROBE_UNROLLS"), unrolls);
+    parse(getenv("PROBE_NT"), nts);
+    if (unrolls.empty()) unrolls.push_back(8);
+    if (nts.empty()) nts.push_back(1);
+    for (long nt : nts)
+      for (long un : unrolls)
+        for (long gsz : grids) {
+          CHECK_PT(ctx, pt_ctx_set_option(ctx, "adamw_nt", nt));
+          CHECK_PT(ctx, pt_ctx_set_option(ctx, "adamw_unroll", un));
+          CHECK_PT(ctx, pt_ctx_set_option(ctx, "adamw_grid", gsz));
+          float best = 1e30f;
+          for (int k = 0; k < 3; ++k) {
+            CHECK_PT(ctx, pt_step_override(ctx, 0.0121f, 0, st));
+            CHECK_HIP(hipEventRecord(e[0], st));
+            CHECK_PT(ctx, pt_chunk_adamw_step(ctx, &hpar, 0, C, g.data(), w.data(), m.data(), v.data(), p.data(), st));
+            CHECK_HIP(hipEventRecord(e[1], st));
+            CHECK_PT(ctx, pt_step_end(ctx, st));
+            CHECK_HIP(hipStreamSynchronize(st));
+            float t;
+            CHECK_HIP(hipEventElapsedTime(&t, e[0], e[1]));
+            if (t < best) best = t;
+          }
+          printf("adamw nt %ld unroll %ld grid %7ld: best of 3 %.3f ms (%.0f GB/s)\n", nt, un, gsz, best,
+                 28.0 * double(S) * C / best / 1e6);
+        }
+  }
   // standalone norm over all chunks (reads 2 bytes per element)
   {
     CHECK_HIP(hipEventRecord(e[0], st));
@@ -130,14 +164,16 @@ int main(int argc, char** argv) {
     CHECK_PT(ctx, pt_step_end(ctx, st));
   }
   for (int k = 0; k < copies; ++k) {
+    // 16 back-to-back copies between different arrays (4 GiB read + 4 GiB written): far beyond any cache
+    const int reps = C >= 17 ? 16 : 1;
     CHECK_HIP(hipEventRecord(e[0], st));
-    CHECK_PT(nullptr, pt_calib_copy(m[(k + 1) % C], v[k % C], 4 * S, st));
+    for (int r = 0; r < reps; ++r) CHECK_PT(nullptr, pt_calib_copy(m[(k + r + 1) % C], v[(k + r) % C], 4 * S, st));
     CHECK_HIP(hipEventRecord(e[1], st));
     CHECK_HIP(hipStreamSynchronize(st));
     float t;
     CHECK_HIP(hipEventElapsedTime(&t, e[0], e[1]));
-    printf("calib copy %d: %llu bytes read + written in %.3f ms (%.0f GB/s)\n", k, (unsigned long long)(4 * S), t,
-           8.0 * double(S) / t / 1e6);
+    printf("calib copy %d: %d x %llu bytes read + written in %.3f ms (%.0f GB/s)\n", k, reps,
+           (unsigned long long)(4 * S), t, reps * 8.0 * double(S) / t / 1e6);
   }
   CHECK_PT(ctx, pt_pack_plan_destroy(plan));
   CHECK_PT(ctx, pt_ctx_destroy(ctx));
