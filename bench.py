@@ -31,8 +31,8 @@ PACK_BYTES_PER_ELEM = 4            # read 2 + write 2
 # HBM traffic of one AdamW launch from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by the
 # same counters on pt_calib_copy); filled from the summaries under profiles/.  bytes per launch.
 MEASURED_TRAFFIC = {
-    # profiles/k_adamw_llama7b_hbm_traffic.md: (46 334 987.97 x 1.99978 + 92 671 995.88 x 0.99998) KiB
-    "llama_7b": 189_778_112_000,
+    # profiles/k_adamw_llama7b_hbm_traffic.md: (46 335 018.56 x 1.999802 + 92 669 643.59 x 0.999987) KiB
+    "llama_7b": 189_777_205_248,
 }
 
 
@@ -369,7 +369,7 @@ def main() -> int:
         "kernels_ms": {"pack_grads+chunk_reduce": round(mean(pack_ms), 4), "finalize": round(mean(norm_ms), 4),
                        "adamw(+prepare)": round(mean(adamw_ms), 4)},
         "step_report": {"norm": rep.norm, "clip_coef": rep.clip_coef, "found_inf": rep.found_inf, "step": rep.step},
-        "roofline": {"kernel": "k_adamw<bf16>", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+        "roofline": {"kernel": "k_adamw<bf16, unroll 4, non-temporal>", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": MEASURED_TRAFFIC.get(args.workload),
                      "bytes_per_launch": adamw_bytes, "avg_launch_ms": round(mean(adamw_ms), 4)},
