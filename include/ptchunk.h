@@ -129,7 +129,8 @@ int pt_ctx_set_state(pt_ctx* ctx, int32_t step, double loss_scale, int32_t good_
  * changes a result bit).
  *   "adamw_grid"    workgroups of the update kernel; 0 = the library's default
  *   "adamw_unroll"  4-element units a lane loads before it computes: 1, 2, 4 or 8
- *   "adamw_nt"      1 = non-temporal hints on the update's loads and stores (default), 0 = none */
+ *   "adamw_nt"      1 = non-temporal hints on the update's loads and stores (default), 0 = none
+ *   "pack_tile_elems"  elements one workgroup of pack/unpack moves; read by pt_pack_plan_create */
 int pt_ctx_set_option(pt_ctx* ctx, const char* name, int64_t value);
 
 /* ---- layout (host, integer only) ---------------------------------------------------

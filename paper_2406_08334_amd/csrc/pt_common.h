@@ -57,13 +57,13 @@ constexpr uint32_t PT_MAX_SLOTS = 8;
 constexpr uint32_t PT_ADAMW_MIN_GRID = 16384;      // default grid of the update kernel: max(this, tiles / 3)
 constexpr uint32_t PT_ADAMW_DEFAULT_UNROLL = 4;
 constexpr uint32_t PT_NORM_BLOCK_ELEMS = 32768;  // elements one block of the norm kernel reduces
-constexpr uint32_t PT_PACK_TILE_ELEMS = 16384;   // chunk-space tile of the pack kernel
+constexpr uint32_t PT_PACK_TILE_ELEMS = 8192;    // chunk-space tile of the pack kernel (one 4-vector batch per lane)
 
 struct PtTile {        // one block of work of the pack / unpack kernels
   uint64_t tensor_addr;  // byte address of the first element on the tensor side
   uint64_t chunk_off;    // first element on the chunk side
   uint32_t chunk;
-  uint32_t len;          // 1 .. PT_PACK_TILE_ELEMS
+  uint32_t len;          // 1 .. tile size of the plan
 };
 
 struct pt_pack_plan {
@@ -88,6 +88,7 @@ struct pt_ctx {
   uint32_t opt_adamw_grid = 0;      // workgroups of the update kernel; 0 = max(PT_ADAMW_MIN_GRID, tiles / 3)
   uint32_t opt_adamw_unroll = PT_ADAMW_DEFAULT_UNROLL;  // 4-element units per lane per tile: 1, 2, 4 or 8
   uint32_t opt_adamw_nt = 1;        // non-temporal hints on the update's loads and stores
+  uint32_t opt_pack_tile_elems = PT_PACK_TILE_ELEMS;  // read when a pack plan is created
   bool scaler = false;
 
   PtDevState* d_state = nullptr;

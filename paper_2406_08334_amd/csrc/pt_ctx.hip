@@ -202,6 +202,11 @@ extern "C" int pt_ctx_set_option(pt_ctx* ctx, const char* name, int64_t value) {
     ctx->opt_adamw_unroll = uint32_t(value);
     return PT_OK;
   }
+  if (std::strcmp(name, "pack_tile_elems") == 0) {
+    if (value < 1024 || value > (1 << 26)) return pt_fail(ctx, PT_ERR_INVALID_ARG, "pack_tile_elems must be in [1024, 2^26]");
+    ctx->opt_pack_tile_elems = uint32_t(value);
+    return PT_OK;
+  }
   if (std::strcmp(name, "adamw_nt") == 0) {
     ctx->opt_adamw_nt = value != 0;
     return PT_OK;

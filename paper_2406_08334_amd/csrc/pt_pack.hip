@@ -3,7 +3,7 @@
 // non-finite scan.
 //
 // HBM-bound: 2 bytes read + 2 bytes written per element.  Tiles are cut in
-// CHUNK space at multiples of PT_PACK_TILE_ELEMS, so many tiny tensors and a few
+// CHUNK space at multiples of the tile size (PT_PACK_TILE_ELEMS by default), so many tiny tensors and a few
 // huge ones give equally sized blocks.  Words are moved as 16-bit integers,
 // never through a float.  The 16-byte vector body is aligned on the destination;
 // when source and destination are not congruent modulo 16 bytes the source side
@@ -192,7 +192,8 @@ extern "C" int pt_pack_plan_create(pt_ctx* ctx, const pt_segment* segs, uint32_t
     if (p.chunk == q.chunk && p.chunk_off + p.len > q.chunk_off)
       return pt_fail(ctx, PT_ERR_INVALID_ARG, "segments %u and %u overlap in chunk %u", order[k - 1], order[k], p.chunk);
   }
-  // cut into tiles at multiples of PT_PACK_TILE_ELEMS in chunk space
+  // cut into tiles at multiples of the tile size in chunk space
+  const uint64_t tile_elems = ctx->opt_pack_tile_elems;
   std::vector<PtTile> tiles;
   std::vector<uint32_t> begin(size_t(ctx->C) + 1, 0);
   uint64_t total = 0;
@@ -201,7 +202,7 @@ extern "C" int pt_pack_plan_create(pt_ctx* ctx, const pt_segment* segs, uint32_t
     uint64_t done = 0;
     while (done < s.len) {
       uint64_t coff = s.chunk_off + done;
-      uint64_t room = PT_PACK_TILE_ELEMS - (coff % PT_PACK_TILE_ELEMS);
+      uint64_t room = tile_elems - (coff % tile_elems);
       uint64_t run = std::min<uint64_t>(room, s.len - done);
       PtTile t;
       t.tensor_addr = uint64_t(reinterpret_cast<uintptr_t>(s.src)) + 2 * (s.src_off + done);

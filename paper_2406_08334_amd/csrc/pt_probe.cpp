@@ -118,6 +118,27 @@ int main(int argc, char** argv) {
     printf("step %d: pack %.3f ms (%.0f GB/s)  finalize %.3f ms  adamw %.3f ms (%.0f GB/s)  norm %.6f step %d\n", s,
            t_pack, 4.0 * n / t_pack / 1e6, t_norm, t_adamw, 28.0 * n / t_adamw / 1e6, rep.norm, rep.step);
   }
+  // PROBE_PACK_TILES="8192,16384,...": times pack with plans of each tile size, same process
+  if (const char* tl = getenv("PROBE_PACK_TILES")) {
+    for (const char* q = tl; *q;) {
+      char* end; long te = strtol(q, &end, 10); q = (*end == ',') ? end + 1 : end;
+      CHECK_PT(ctx, pt_ctx_set_option(ctx, "pack_tile_elems", te));
+      pt_pack_plan* pl = nullptr;
+      CHECK_PT(ctx, pt_pack_plan_create(ctx, segs.data(), C, &pl));
+      float best = 1e30f;
+      for (int k = 0; k < 4; ++k) {
+        CHECK_HIP(hipEventRecord(e[0], st));
+        CHECK_PT(ctx, pt_chunk_pack_grads(ctx, pl, g.data(), st));
+        CHECK_HIP(hipEventRecord(e[1], st));
+        CHECK_HIP(hipStreamSynchronize(st));
+        float t; CHECK_HIP(hipEventElapsedTime(&t, e[0], e[1]));
+        if (t < best) best = t;
+      }
+      printf("pack tile %8ld: best of 4 %.3f ms (%.0f GB/s)\n", te, best, 4.0 * double(S) * C / best / 1e6);
+      CHECK_PT(ctx, pt_pack_plan_destroy(pl));
+      if (end == q && *q) break;
+    }
+  }
   // PROBE_GRIDS="4096,16384,..." [PROBE_UNROLLS="4,8"] [PROBE_NT="1,0"]: times the update alone for
   // every combination, in this one process on these allocations (placement differs run to run)
   if (const char* gl = getenv("PROBE_GRIDS")) {
