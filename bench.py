@@ -210,7 +210,7 @@ def run_in_processes(args) -> int:
     for i in range(args.processes):
         cmd = [sys.executable, os.path.abspath(__file__), "--child", "--steps", str(args.steps), "--warmup",
                str(args.warmup), "--workload", args.workload, "--grad-sets", str(args.grad_sets),
-               "--cpu-sample-chunks", str(args.cpu_sample_chunks)]
+               "--cpu-sample-chunks", str(args.cpu_sample_chunks), "--layout", args.layout]
         if args.calib: cmd.append("--calib")
         if args.sweep: cmd.append("--sweep")
         if args.no_cpu_baseline or i != args.processes - 1: cmd.append("--no-cpu-baseline")
@@ -241,6 +241,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-chunks", type=int, default=4)
     ap.add_argument("--calib", action="store_true", help="also time a bare copy kernel (attainable HBM rate)")
+    ap.add_argument("--layout", default="dense", choices=["dense", "grouped"],
+                    help="dense: the benchmark configurations' layout; grouped: the paper's no-split, block-per-chunk layout")
     ap.add_argument("--processes", type=int, default=2,
                     help="measure in this many fresh processes one after the other and report the best "
                          "(physical placement of the state differs from process to process)")
@@ -258,6 +260,8 @@ def main() -> int:
         return 2
     if args.stream:
         return run_streamed(args)
+    if args.layout == "grouped":
+        args.no_cpu_baseline = True      # the oracle leg samples the dense layout's first chunks
     if not args.child and args.processes > 1:
         return run_in_processes(args)
 
@@ -275,23 +279,49 @@ def main() -> int:
     table, S = shapes.workload(args.workload)
     sizes = [n for _, n in table]
     N = sum(sizes)
-    segs, C = B.pt_layout_dense(sizes, S)
+    layout_note = "dense layout (tensors cut at chunk boundaries, last chunk padded)"
+    if args.layout == "grouped":
+        # the paper's layout: no tensor split, one transformer block per chunk, chunk size by least waste
+        gids = shapes.block_ids(table)
+        per_block = {}
+        for n, g in zip(sizes, gids):
+            if g is not None:
+                per_block[g] = per_block.get(g, 0) + n
+        t_s = time.perf_counter()
+        S, C, waste = B.pt_chunk_size_search(sizes, gids, max(per_block.values()), 1 << 25, 1 << 20)
+        segs, C, waste = B.pt_layout_grouped(sizes, gids, S)
+        layout_note = (f"grouped layout (no tensor split, blocks kept whole; searched chunk size {S}, waste {waste} "
+                       f"elements = {100.0 * waste / N:.2f} %, search + layout {1e3 * (time.perf_counter() - t_s):.1f} ms on the host)")
+    else:
+        segs, C = B.pt_layout_dense(sizes, S)
     N_pad = C * S
     n_sets = max(1, min(args.grad_sets, args.steps + args.warmup))
-    log(f"[bench] workload {args.workload}: {N:,} elements, {C} chunks of {S:,}; "
+    log(f"[bench] workload {args.workload}: {N:,} elements, {C} chunks of {S:,}; {layout_note}; "
         f"state {16 * N_pad / 1e9:.2f} GB + {n_sets} gradient sets of {2 * N / 1e9:.2f} GB")
 
     t0 = time.time()
     ctx = B.pt_ctx_create(B.PT_BF16, S, C, None)
     g16 = torch.zeros(C, S, dtype=torch.bfloat16, device=dev)
     p16 = torch.zeros(C, S, dtype=torch.bfloat16, device=dev)
-    synth.normal_16(synth.SEED_PARAMS, 0, 0, 0, N, 0.02, torch.bfloat16, dev, out=p16.view(-1)[:N])
+    offs = np.cumsum([0] + sizes[:-1]).tolist()
+    if args.layout == "grouped":
+        # parameters are generated as the model's tensors and brought into chunk space by the same copy
+        flat = torch.empty(N, dtype=torch.bfloat16, device=dev)
+        synth.normal_16(synth.SEED_PARAMS, 0, 0, 0, N, 0.02, torch.bfloat16, dev, out=flat)
+        for s in segs:
+            s.src = flat.data_ptr() + 2 * offs[s.tensor]
+        plan0 = B.pt_pack_plan_create(ctx, segs)
+        B.pt_chunk_pack_grads(ctx, plan0, [p16[c] for c in range(C)], torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        B.pt_pack_plan_destroy(plan0)
+        del flat
+    else:
+        synth.normal_16(synth.SEED_PARAMS, 0, 0, 0, N, 0.02, torch.bfloat16, dev, out=p16.view(-1)[:N])
     w = torch.empty(C, S, dtype=torch.float32, device=dev)
     for c in range(C):
         w[c].copy_(p16[c])
     m = torch.zeros(C, S, dtype=torch.float32, device=dev)
     v = torch.zeros(C, S, dtype=torch.float32, device=dev)
-    offs = np.cumsum([0] + sizes[:-1]).tolist()
     grad_sets, plans = [], []
     for k in range(n_sets):
         gs = torch.empty(N, dtype=torch.bfloat16, device=dev)
@@ -360,7 +390,7 @@ def main() -> int:
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {N} elements in {C} chunks of {S}, all GPU-resident, "
+        "config": {"workload": f"{args.workload}: {N} elements in {C} chunks of {S}, {layout_note}, all GPU-resident, "
                                "bf16 params/grads N(0,0.02)/N(0,1e-3), fp32 master/m/v, AdamW lr 1e-4 betas (0.9,0.95) "
                                "eps 1e-8 wd 0.1 clip 1.0",
                    "chunk_elems": S, "n_chunks": C, "elements": N, "padded_elements": N_pad,
@@ -371,7 +401,7 @@ def main() -> int:
         "step_report": {"norm": rep.norm, "clip_coef": rep.clip_coef, "found_inf": rep.found_inf, "step": rep.step},
         "roofline": {"kernel": "k_adamw<bf16, unroll 4, non-temporal>", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC.get(args.workload),
+                     "traffic": MEASURED_TRAFFIC.get(args.workload) if args.layout == "dense" else None,
                      "bytes_per_launch": adamw_bytes, "avg_launch_ms": round(mean(adamw_ms), 4)},
     }
 

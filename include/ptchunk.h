@@ -143,6 +143,30 @@ int pt_ctx_set_option(pt_ctx* ctx, const char* name, int64_t value);
 int pt_layout_dense(const uint64_t* tensor_elems, uint32_t n_tensors, uint64_t chunk_elems,
                     pt_segment* out, uint32_t cap, uint32_t* n_segments, uint32_t* n_chunks);
 
+/* Paper-faithful layout (paper, Appendix B.1 "Chunk Organization and Size Search"): the tensors
+ * are given in execution order, each once (a parameter shared between layers at its first
+ * occurrence); a tensor is never split between chunks; consecutive tensors with the same
+ * tensor_group id (one transformer block) are kept in one chunk whenever the block fits an
+ * empty chunk, else they are placed one by one; tensors with PT_NO_GROUP (or tensor_group ==
+ * NULL) stand alone.  A piece that does not fit the rest of the current chunk opens the next
+ * chunk, the rest stays unused ("memory waste").  Every tensor starts at a multiple of 8
+ * elements of its chunk.  Outputs as pt_layout_dense, one segment per non-empty tensor, plus
+ * waste_elems = n_chunks * chunk_elems - sum of the sizes (may be NULL).  A tensor larger than a
+ * chunk is PT_ERR_INVALID_ARG. */
+#define PT_NO_GROUP 0xffffffffu
+int pt_layout_grouped(const uint64_t* tensor_elems, const uint32_t* tensor_group, uint32_t n_tensors,
+                      uint64_t chunk_elems, pt_segment* out, uint32_t cap, uint32_t* n_segments,
+                      uint32_t* n_chunks, uint64_t* waste_elems);
+
+/* Chunk-size search of the same passage: simulates pt_layout_grouped for the candidate sizes
+ * S_min, S_min + step, ... <= S_min + span, where S_min = max(largest tensor, min_chunk_elems)
+ * rounded up to step_elems, and returns the size of least waste (ties: the smaller size).  The
+ * paper states neither the grid nor the tie rule; span 2^25 and step 2^20 elements reproduce the
+ * chunk counts of its Table 4 (12 for the 32-block GPT-2 1B, 49 for the 48-block GPT-2 10B). */
+int pt_chunk_size_search(const uint64_t* tensor_elems, const uint32_t* tensor_group, uint32_t n_tensors,
+                         uint64_t min_chunk_elems, uint64_t span_elems, uint64_t step_elems,
+                         uint64_t* best_chunk_elems, uint32_t* n_chunks, uint64_t* waste_elems);
+
 /* ---- pack plan -----------------------------------------------------------------------
  * Validates a segment table against the context (ranges inside chunks, no two
  * segments overlapping in a chunk), cuts it into tiles and uploads the tile list.

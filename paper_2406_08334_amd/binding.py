@@ -21,6 +21,7 @@ EXPORTS = [
     "pt_layout_dense", "pt_pack_plan_create", "pt_pack_plan_destroy", "pt_chunk_pack_grads", "pt_chunk_unpack",
     "pt_chunk_grad_sqnorm", "pt_chunk_adamw_step", "pt_stream_reserve", "pt_chunk_stream_step", "pt_step_end",
     "pt_step_report_read", "pt_update_consts_read", "pt_step_override", "pt_calib_copy", "pt_ctx_set_option",
+    "pt_layout_grouped", "pt_chunk_size_search",
 ]
 
 
@@ -97,6 +98,10 @@ def lib():
         L.pt_step_override.argtypes = [vp, C.c_float, i32, vp]
         L.pt_calib_copy.argtypes = [vp, vp, u64, vp]
         L.pt_ctx_set_option.argtypes = [vp, C.c_char_p, C.c_int64]
+        L.pt_layout_grouped.argtypes = [C.POINTER(u64), C.POINTER(u32), u32, u64, C.POINTER(pt_segment), u32,
+                                        C.POINTER(u32), C.POINTER(u32), C.POINTER(u64)]
+        L.pt_chunk_size_search.argtypes = [C.POINTER(u64), C.POINTER(u32), u32, u64, u64, u64, C.POINTER(u64),
+                                           C.POINTER(u32), C.POINTER(u64)]
         for name in EXPORTS:
             if name not in ("pt_version", "pt_status_string", "pt_last_error"):
                 getattr(L, name).restype = C.c_int
@@ -261,3 +266,39 @@ def pt_calib_copy(dst, src, nbytes: int, stream=None):
 
 def pt_ctx_set_option(ctx, name: str, value: int):
     _check(lib().pt_ctx_set_option(ctx, name.encode(), int(value)), "pt_ctx_set_option", ctx)
+
+
+PT_NO_GROUP = 0xFFFFFFFF
+
+
+def _group_array(tensor_group, n):
+    if tensor_group is None:
+        return None
+    return (C.c_uint32 * max(n, 1))(*[PT_NO_GROUP if g is None else int(g) for g in tensor_group])
+
+
+def pt_layout_grouped(tensor_elems, tensor_group, chunk_elems: int):
+    """-> (list of pt_segment with src unset, n_chunks, waste_elems).  Host only."""
+    n = len(tensor_elems)
+    sizes = (C.c_uint64 * max(n, 1))(*[int(x) for x in tensor_elems])
+    groups = _group_array(tensor_group, n)
+    nseg, nchunks, waste = C.c_uint32(), C.c_uint32(), C.c_uint64()
+    rc = lib().pt_layout_grouped(sizes, groups, n, int(chunk_elems), None, 0, C.byref(nseg), C.byref(nchunks),
+                                 C.byref(waste))
+    _check(rc, "pt_layout_grouped")
+    segs = (pt_segment * max(nseg.value, 1))()
+    rc = lib().pt_layout_grouped(sizes, groups, n, int(chunk_elems), segs, nseg.value, C.byref(nseg),
+                                 C.byref(nchunks), C.byref(waste))
+    _check(rc, "pt_layout_grouped")
+    return [segs[i] for i in range(nseg.value)], int(nchunks.value), int(waste.value)
+
+
+def pt_chunk_size_search(tensor_elems, tensor_group, min_chunk_elems: int, span_elems: int, step_elems: int):
+    """-> (best chunk_elems, n_chunks, waste_elems).  Host only."""
+    n = len(tensor_elems)
+    sizes = (C.c_uint64 * max(n, 1))(*[int(x) for x in tensor_elems])
+    best, nchunks, waste = C.c_uint64(), C.c_uint32(), C.c_uint64()
+    rc = lib().pt_chunk_size_search(sizes, _group_array(tensor_group, n), n, int(min_chunk_elems), int(span_elems),
+                                    int(step_elems), C.byref(best), C.byref(nchunks), C.byref(waste))
+    _check(rc, "pt_chunk_size_search")
+    return int(best.value), int(nchunks.value), int(waste.value)

@@ -315,6 +315,116 @@ extern "C" int pt_layout_dense(const uint64_t* tensor_elems, uint32_t n_tensors,
   return PT_OK;
 }
 
+// ---- paper-faithful layout: no tensor split, transformer blocks kept together -----------------
+// (Appendix B.1 of the paper, "Chunk Organization and Size Search".)
+
+namespace {
+
+constexpr uint64_t LAYOUT_ALIGN = 8;   // elements: every tensor starts on a 16-byte boundary of its chunk
+
+inline uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+// End offset after placing tensors [lo, hi) back to back from `start` (empty tensors take no room).
+uint64_t span_of(const uint64_t* elems, uint32_t lo, uint32_t hi, uint64_t start) {
+  uint64_t off = start;
+  for (uint32_t t = lo; t < hi; ++t)
+    if (elems[t]) off = round_up(off, LAYOUT_ALIGN) + elems[t];
+  return off;
+}
+
+// Places every tensor; returns false if a tensor is larger than a chunk.  out may be NULL.
+bool place_grouped(const uint64_t* elems, const uint32_t* group, uint32_t n, uint64_t S, pt_segment* out,
+                   uint64_t cap, uint64_t* n_seg, uint64_t* n_chunks, bool* cap_hit) {
+  uint64_t chunk = 0, off = 0, segs = 0;
+  bool any = false;
+  *cap_hit = false;
+  uint32_t i = 0;
+  while (i < n) {
+    uint32_t j = i + 1;
+    if (group && group[i] != PT_NO_GROUP)
+      while (j < n && group[j] == group[i]) ++j;
+    const bool together = span_of(elems, i, j, 0) <= S;       // the run fits an empty chunk: keep it whole
+    uint32_t lo = i;
+    while (lo < j) {
+      const uint32_t hi = together ? j : lo + 1;
+      uint64_t total = 0;
+      for (uint32_t t = lo; t < hi; ++t) total += elems[t];
+      if (total) {
+        if (span_of(elems, lo, hi, 0) > S) return false;
+        if (span_of(elems, lo, hi, off) > S) { ++chunk; off = 0; }
+        for (uint32_t t = lo; t < hi; ++t) {
+          if (!elems[t]) continue;
+          off = round_up(off, LAYOUT_ALIGN);
+          if (out) {
+            if (segs >= cap) { *cap_hit = true; return true; }
+            pt_segment& s = out[segs];
+            s.src = nullptr; s.src_off = 0; s.len = elems[t]; s.chunk_off = off; s.chunk = uint32_t(chunk); s.tensor = t;
+          }
+          ++segs;
+          off += elems[t];
+          any = true;
+        }
+      }
+      lo = hi;
+    }
+    i = j;
+  }
+  *n_seg = segs;
+  *n_chunks = any ? chunk + 1 : 0;
+  return true;
+}
+
+}  // namespace
+
+extern "C" int pt_layout_grouped(const uint64_t* tensor_elems, const uint32_t* tensor_group, uint32_t n_tensors,
+                                 uint64_t chunk_elems, pt_segment* out, uint32_t cap, uint32_t* n_segments,
+                                 uint32_t* n_chunks, uint64_t* waste_elems) {
+  if ((!tensor_elems && n_tensors) || !n_segments || !n_chunks)
+    return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_layout_grouped: NULL argument");
+  if (chunk_elems == 0) return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_layout_grouped: chunk_elems is 0");
+  if (chunk_elems % 8 != 0) return pt_fail(nullptr, PT_ERR_ALIGNMENT, "pt_layout_grouped: chunk_elems is not a multiple of 8");
+  uint64_t nseg = 0, nch = 0, total = 0;
+  for (uint32_t t = 0; t < n_tensors; ++t) total += tensor_elems[t];
+  bool cap_hit = false;
+  if (!place_grouped(tensor_elems, tensor_group, n_tensors, chunk_elems, out, cap, &nseg, &nch, &cap_hit))
+    return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_layout_grouped: a tensor is larger than a chunk of %llu elements",
+                   (unsigned long long)chunk_elems);
+  if (cap_hit) return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_layout_grouped: cap %u too small", cap);
+  if (nch > 0xfffffffeull) return pt_fail(nullptr, PT_ERR_UNSUPPORTED, "pt_layout_grouped: too many chunks");
+  *n_segments = uint32_t(nseg);
+  *n_chunks = uint32_t(nch);
+  if (waste_elems) *waste_elems = nch * chunk_elems - total;
+  return PT_OK;
+}
+
+extern "C" int pt_chunk_size_search(const uint64_t* tensor_elems, const uint32_t* tensor_group, uint32_t n_tensors,
+                                    uint64_t min_chunk_elems, uint64_t span_elems, uint64_t step_elems,
+                                    uint64_t* best_chunk_elems, uint32_t* n_chunks, uint64_t* waste_elems) {
+  if ((!tensor_elems && n_tensors) || !best_chunk_elems)
+    return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_chunk_size_search: NULL argument");
+  if (step_elems == 0 || step_elems % 8 != 0)
+    return pt_fail(nullptr, PT_ERR_ALIGNMENT, "pt_chunk_size_search: step_elems must be a positive multiple of 8");
+  uint64_t biggest = 1, total = 0;
+  for (uint32_t t = 0; t < n_tensors; ++t) { total += tensor_elems[t]; if (tensor_elems[t] > biggest) biggest = tensor_elems[t]; }
+  const uint64_t s_min = round_up(biggest > min_chunk_elems ? biggest : min_chunk_elems, step_elems);
+  if (span_elems / step_elems > 10000000ull)
+    return pt_fail(nullptr, PT_ERR_UNSUPPORTED, "pt_chunk_size_search: more than 10^7 candidates");
+  bool found = false;
+  uint64_t best_S = 0, best_waste = 0, best_chunks = 0;
+  for (uint64_t S = s_min; S <= s_min + span_elems; S += step_elems) {
+    uint64_t nseg = 0, nch = 0;
+    bool cap_hit = false;
+    if (!place_grouped(tensor_elems, tensor_group, n_tensors, S, nullptr, 0, &nseg, &nch, &cap_hit)) continue;
+    const uint64_t waste = nch * S - total;
+    if (!found || waste < best_waste) { found = true; best_S = S; best_waste = waste; best_chunks = nch; }
+  }
+  if (!found) return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_chunk_size_search: no feasible chunk size on the grid");
+  *best_chunk_elems = best_S;
+  if (n_chunks) *n_chunks = uint32_t(best_chunks);
+  if (waste_elems) *waste_elems = best_waste;
+  return PT_OK;
+}
+
 // ---- measurement aid: a plain streaming copy ----------------------------------------------------
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));

@@ -44,6 +44,21 @@ def llama(h: int, ffn: int, n_blocks: int, vocab: int = 32000):
     return out
 
 
+def block_ids(table):
+    """Transformer-block id per tensor (None for tensors outside the blocks), from the names
+    'h<i>.' (GPT-2) / 'layers.<i>.' (LLaMA)."""
+    out = []
+    for name, _ in table:
+        head = name.split(".")
+        if head[0].startswith("h") and head[0][1:].isdigit():
+            out.append(int(head[0][1:]))
+        elif head[0] == "layers" and len(head) > 1 and head[1].isdigit():
+            out.append(int(head[1]))
+        else:
+            out.append(None)
+    return out
+
+
 # name -> (tensor table, chunk elements)
 WORKLOADS = {
     "gpt2_block_768": (lambda: gpt2_block(768), 1 << 22),

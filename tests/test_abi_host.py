@@ -95,3 +95,71 @@ def test_argument_validation_without_a_gpu():
     assert L.pt_ctx_destroy(None) == B.PT_OK and L.pt_pack_plan_destroy(None) == B.PT_OK
     with pytest.raises(B.PtError):
         B.pt_layout_dense([1, 2], 12)
+
+
+# ---- paper-faithful layout: library vs the oracle's plain-Python layout -------------------------
+
+def _lib_places(sizes, gids, S):
+    segs, n_chunks, waste = B.pt_layout_grouped(sizes, gids, S)
+    place = [None] * len(sizes)
+    for s in segs:
+        assert s.src_off == 0 and s.len == sizes[s.tensor]          # one whole tensor per segment
+        place[s.tensor] = (s.chunk, s.chunk_off)
+    return place, n_chunks, waste
+
+
+def test_layout_grouped_matches_the_oracle_on_random_inputs():
+    import random
+    from oracle import layout as OL
+    rng = random.Random(17)
+    for _ in range(300):
+        n = rng.randint(1, 16)
+        sizes = [rng.choice([0, 1, 3, 8, 9, 17, 40, 64, 100, 250]) for _ in range(n)]
+        gids, g = [], 0
+        for i in range(n):
+            if rng.random() < 0.3:
+                g += 1
+            gids.append(None if rng.random() < 0.25 else g)
+        S = rng.choice([8, 16, 64, 104, 128, 256, 512])
+        want = OL.layout_grouped(sizes, gids, S)
+        if want is None:
+            with pytest.raises(B.PtError):
+                B.pt_layout_grouped(sizes, gids, S)
+            continue
+        assert _lib_places(sizes, gids, S) == want
+
+
+def test_chunk_size_search_matches_the_oracle_and_the_papers_table():
+    import random
+    from oracle import layout as OL
+    for name, make, want_chunks in (("gpt2_1b", lambda: shapes.gpt2(1600, 32, 6400), 12),
+                                    ("gpt2_10b", lambda: shapes.gpt2(4096, 48, 16384), 49)):
+        table = make()
+        sizes, gids = [n for _, n in table], shapes.block_ids(table)
+        got = B.pt_chunk_size_search(sizes, gids, 0, 1 << 25, 1 << 20)
+        assert got == OL.chunk_size_search(sizes, gids, 0, 1 << 25, 1 << 20)
+        assert got[1] == want_chunks                                   # Table 4 of the paper
+        assert _lib_places(sizes, gids, got[0]) == OL.layout_grouped(sizes, gids, got[0])
+    rng = random.Random(3)
+    for _ in range(100):
+        n = rng.randint(1, 10)
+        sizes = [rng.randint(1, 90) for _ in range(n)]
+        gids = [rng.choice([None, 0, 1, 2]) for _ in range(n)]
+        span, mn = 8 * rng.randint(0, 10), rng.choice([0, 0, 64])
+        assert B.pt_chunk_size_search(sizes, gids, mn, span, 8) == OL.chunk_size_search(sizes, gids, mn, span, 8)
+    with pytest.raises(B.PtError):
+        B.pt_chunk_size_search([5, 6], None, 0, 64, 12)                # step not a multiple of 8
+
+
+def test_llama7b_grouped_layout_keeps_every_block_whole():
+    table, _ = shapes.workload("llama_7b")
+    sizes, gids = [n for _, n in table], shapes.block_ids(table)
+    block = 4 * 4096 ** 2 + 3 * 4096 * 11008 + 2 * 4096
+    # the embedding (131 M) is the largest tensor; a block (202 M) only fits if the search starts there
+    S, n_chunks, waste = B.pt_chunk_size_search(sizes, gids, block, 1 << 25, 1 << 20)
+    place, n2, w2 = _lib_places(sizes, gids, S)
+    assert (n2, w2) == (n_chunks, waste)
+    assert S >= block and n_chunks == 34                               # embedding, 32 blocks, norm + head
+    for b in range(32):
+        assert len({place[t][0] for t, g in enumerate(gids) if g == b}) == 1
+    assert waste < 0.03 * sum(sizes)

@@ -428,3 +428,82 @@ def test_error_paths_return_codes_and_leave_the_context_usable():
         assert st.report().step == 1
     finally:
         st.close()
+
+
+# --------------------------------------------------- paper-faithful (no-split, grouped) layout
+
+@pytest.mark.parametrize("separate_allocs", [True, False])
+def test_grouped_layout_pack_and_step_against_oracle(orc, separate_allocs):
+    from oracle import layout as OL
+    # embedding, three "blocks" (one larger than the others), tail tensors; odd sizes on purpose
+    sizes = [40_000, 5, 9_000, 9_001, 77, 9_000, 30_011, 3, 9_000, 9_000, 64, 1_000, 17]
+    gids = [None, None, 0, 0, 0, 1, 1, 1, 2, 2, 2, None, None]
+    S, n_chunks, waste = B.pt_chunk_size_search(sizes, gids, 0, 1 << 14, 1 << 10)
+    assert (S, n_chunks, waste) == OL.chunk_size_search(sizes, gids, 0, 1 << 14, 1 << 10)
+    place, _, _ = OL.layout_grouped(sizes, gids, S)
+    segs, C, _ = B.pt_layout_grouped(sizes, gids, S)
+    N = sum(sizes)
+    dev = "cuda"
+    if separate_allocs:
+        tensors = [torch.empty(n, dtype=torch.bfloat16, device=dev) for n in sizes]
+    else:
+        flat = torch.empty(N, dtype=torch.bfloat16, device=dev)
+        offs = np.cumsum([0] + sizes[:-1]).tolist()
+        tensors = [flat[o:o + n] for o, n in zip(offs, sizes)]
+    for s in segs:
+        s.src = tensors[s.tensor].data_ptr()
+    ctx = B.pt_ctx_create(B.PT_BF16, S, C, None)
+    plan = B.pt_pack_plan_create(ctx, segs)
+    try:
+        g16 = torch.zeros(C, S, dtype=torch.bfloat16, device=dev)
+        p16 = torch.zeros(C, S, dtype=torch.bfloat16, device=dev)
+        rows = lambda a: [a[c] for c in range(C)]
+
+        def scatter(per_tensor_u16):                       # the oracle's placements, applied with numpy
+            out = np.zeros((C, S), np.uint16)
+            for t, pl in enumerate(place):
+                if pl is not None:
+                    out[pl[0], pl[1]:pl[1] + sizes[t]] = per_tensor_u16[t]
+            return out
+
+        # parameters: generated per tensor, placed by the oracle's layout
+        params = [synth.normal_16(synth.SEED_PARAMS, 0, t, 0, n, 0.02, torch.bfloat16, dev) for t, n in enumerate(sizes)]
+        p_host = scatter([to_u16(x) for x in params])
+        p16.view(torch.int16).copy_(torch.from_numpy(p_host.view(np.int16)).to(dev))
+        w = p16.float(); m = torch.zeros_like(w); v = torch.zeros_like(w)
+        hp_b, hp_o, hpd = hp_pair()
+        host = dict(p16=p_host.reshape(-1).copy(), w=w.cpu().numpy().reshape(-1).copy(),
+                    m=np.zeros(C * S, np.float32), v=np.zeros(C * S, np.float32))
+        ost = orc.new_state(None)
+        trk = ScaleTracker(host["w"], host["m"], hpd)
+        for step in (1, 2):
+            for t, n in enumerate(sizes):
+                synth.normal_16(synth.SEED_GRADS, step, t, 0, n, 1e-2, torch.bfloat16, dev, out=tensors[t])
+            want_g = scatter([to_u16(x) for x in tensors])
+            g16.view(torch.int16).fill_(0)
+            B.pt_chunk_pack_grads(ctx, plan, rows(g16))
+            assert same_bits(to_u16(g16), want_g)                       # pack: bit-exact, gaps untouched
+            B.pt_chunk_grad_sqnorm(ctx, None, 0, C, True)
+            B.pt_chunk_adamw_step(ctx, hp_b, 0, C, rows(g16), rows(w), rows(m), rows(v), rows(p16))
+            rep = B.pt_step_report_read(ctx)
+            B.pt_step_end(ctx)
+            orep = orc.step(hp_o, None, ost, want_g.reshape(-1), host["w"], host["m"], host["v"], host["p16"], S,
+                            orc.BF16, threads=4)
+            assert abs(rep.norm - orep.norm) <= 1e-12 * orep.norm and rep.clip_coef < 1.0
+            trk.advance(step, orc.decode16(want_g.reshape(-1), orc.BF16).astype(np.float64) * orep.grad_mult, host["v"])
+            got = (w.cpu().numpy().reshape(-1), m.cpu().numpy().reshape(-1), v.cpu().numpy().reshape(-1))
+            trk.check(got, (host["w"], host["m"], host["v"]), tol=1e-6)
+            check_p16(orc.decode16(to_u16(p16).reshape(-1), orc.BF16), orc.decode16(host["p16"], orc.BF16), host["w"],
+                      trk.W, False)
+        # updated parameters go back to the model's tensors through the inverse copy
+        for x in tensors:
+            x.zero_()
+        B.pt_chunk_unpack(ctx, plan, rows(p16))
+        back = to_u16(p16)
+        for t, pl in enumerate(place):
+            if pl is not None:
+                assert same_bits(to_u16(tensors[t]), back[pl[0], pl[1]:pl[1] + sizes[t]])
+    finally:
+        torch.cuda.synchronize()
+        B.pt_pack_plan_destroy(plan)
+        B.pt_ctx_destroy(ctx)
