@@ -152,13 +152,17 @@ def run_streamed(args) -> int:
     r_g, r_w, r_m, r_v, r_p = rows(g16), rows(w), rows(m), rows(v), rows(p16)
     pack_rows = r_g + [None] * (C - n_persist)
 
-    def one_step(streamed=True, resident=True):
+    host_threads = args.host_threads if args.host_threads > 0 else (os.cpu_count() or 1)
+
+    def one_step(streamed=True, resident=True, on_host=False):
         B.pt_chunk_pack_grads(ctx, plan, pack_rows, stream)
         B.pt_chunk_grad_sqnorm(ctx, None, 0, C, True, stream)
-        if streamed:
+        if streamed and not on_host:
             B.pt_chunk_stream_step(ctx, hp, n_persist, n_host, h_g, h_w, h_m, h_v, h_p, stream)
         if resident:
             B.pt_chunk_adamw_step(ctx, hp, 0, n_persist, r_g, r_w, r_m, r_v, r_p, stream)
+        if streamed and on_host:        # the paper's placement: host threads, while the GPU kernel runs
+            B.pt_chunk_host_adamw_step(ctx, hp, n_persist, n_host, h_g, h_w, h_m, h_v, h_p, host_threads, stream)
         B.pt_step_end(ctx, stream)
 
     def timed(k, **kw):
@@ -175,6 +179,24 @@ def run_streamed(args) -> int:
     t_step = timed(K)
     t_res = timed(max(K, 3), streamed=False)
     t_str = timed(K, resident=False)
+    host_update = None
+    if args.host_update:
+        t_h = timed(K, on_host=True)
+        t_h_only = timed(K, on_host=True, resident=False)
+        # what still has to cross the link in that variant: 16-bit parameters up (gradients came down during backward)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(n_host):
+            tmp16.copy_(h_p[i], non_blocking=True)
+        torch.cuda.synchronize()
+        t_up = time.perf_counter() - t
+        host_update = {"threads": host_threads, "ms_per_step": round(1e3 * t_h, 2),
+                       "ms_host_chunks_only": round(1e3 * t_h_only, 2),
+                       "host_elements_per_s": round(n_host * S / t_h_only / 1e9, 3),
+                       "host_GBps_at_28B_per_element": round(28 * n_host * S / t_h_only / 1e9, 1),
+                       "overlap_ratio_step_over_max": round(t_h / max(t_h_only, t_res), 4),
+                       "ms_param16_upload_afterwards": round(1e3 * t_up, 2),
+                       "speedup_of_streaming_through_the_gpu": round(t_h / t_step, 3)}
     rep = B.pt_step_report_read(ctx, stream)
     link_bytes = 14 * S * n_host
     per_dir = link_bytes / t_step / 1e9
@@ -193,6 +215,8 @@ def run_streamed(args) -> int:
         "overlap_ratio_step_over_max": round(t_step / max(t_res, t_str), 4),
         "step_report": {"norm": rep.norm, "found_inf": rep.found_inf, "step": rep.step},
     }
+    if host_update:
+        out["host_side_update"] = host_update
     B.pt_pack_plan_destroy(plan)
     B.pt_ctx_destroy(ctx)
     print(json.dumps(out), flush=True)
@@ -253,6 +277,9 @@ def main() -> int:
                          "the rest in pinned host memory through pt_chunk_stream_step")
     ap.add_argument("--host-chunks", type=int, default=0, help="--stream: host-resident chunks (default: all of the second half)")
     ap.add_argument("--slots", type=int, default=3, help="--stream: device chunk buffers")
+    ap.add_argument("--host-update", action="store_true",
+                    help="--stream: also time the paper's placement, host chunks updated by host threads")
+    ap.add_argument("--host-threads", type=int, default=0, help="--host-update: threads (default: all cores)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "

@@ -257,6 +257,20 @@ int pt_chunk_stream_step(pt_ctx* ctx, const pt_hparams* hp, uint32_t first_chunk
                          const void* const* h_grad, float* const* h_master, float* const* h_m,
                          float* const* h_v, void* const* h_param16, void* stream);
 
+/* Update of host-resident chunks ON THE HOST: the paper's own placement (CPU Adam for
+ * non-persistent chunks, running concurrently with GPU work; "Hierarchical Chunk Management for
+ * Model States", Appendix A.1 T_CPU_OPTIM).  Same arithmetic and the same nine fp32 constants
+ * as pt_chunk_adamw_step - the constants are read back from the device, waiting only for the
+ * scalar kernels already queued on `stream`, not for bulk work behind them - so results are
+ * bit-identical to the device paths.  BLOCKING: returns when n_threads host threads (this one
+ * included) have updated master, m, v and param16 of chunks [first_chunk, first_chunk+n_chunks)
+ * in place.  Queue pt_chunk_adamw_step for the resident chunks first and the two run side by
+ * side.  h_*: host arrays of n_chunks host pointers (pinned or not).  A skipped step leaves the
+ * arrays untouched.  Requires a finalized norm in this step. */
+int pt_chunk_host_adamw_step(pt_ctx* ctx, const pt_hparams* hp, uint32_t first_chunk, uint32_t n_chunks,
+                             const void* const* h_grad, float* const* h_master, float* const* h_m,
+                             float* const* h_v, void* const* h_param16, uint32_t n_threads, void* stream);
+
 /* Closes the step: makes `stream` wait for the side streams of a streamed update,
  * then on the device: found_inf ? (loss_scale = max(loss_scale*backoff, 1),
  * good_steps = 0) : (step += 1, good_steps += 1, and loss_scale *= growth when

@@ -21,7 +21,7 @@ EXPORTS = [
     "pt_layout_dense", "pt_pack_plan_create", "pt_pack_plan_destroy", "pt_chunk_pack_grads", "pt_chunk_unpack",
     "pt_chunk_grad_sqnorm", "pt_chunk_adamw_step", "pt_stream_reserve", "pt_chunk_stream_step", "pt_step_end",
     "pt_step_report_read", "pt_update_consts_read", "pt_step_override", "pt_calib_copy", "pt_ctx_set_option",
-    "pt_layout_grouped", "pt_chunk_size_search",
+    "pt_layout_grouped", "pt_chunk_size_search", "pt_chunk_host_adamw_step",
 ]
 
 
@@ -93,6 +93,7 @@ def lib():
         L.pt_stream_reserve.argtypes = [vp, u32]
         L.pt_chunk_stream_step.argtypes = [vp, C.POINTER(pt_hparams), u32, u32, pp, pp, pp, pp, pp, vp]
         L.pt_step_end.argtypes = [vp, vp]
+        L.pt_chunk_host_adamw_step.argtypes = [vp, C.POINTER(pt_hparams), u32, u32, pp, pp, pp, pp, pp, u32, vp]
         L.pt_step_report_read.argtypes = [vp, C.POINTER(pt_step_report), vp]
         L.pt_update_consts_read.argtypes = [vp, C.POINTER(pt_update_consts), vp]
         L.pt_step_override.argtypes = [vp, C.c_float, i32, vp]
@@ -302,3 +303,11 @@ def pt_chunk_size_search(tensor_elems, tensor_group, min_chunk_elems: int, span_
                                     int(step_elems), C.byref(best), C.byref(nchunks), C.byref(waste))
     _check(rc, "pt_chunk_size_search")
     return int(best.value), int(nchunks.value), int(waste.value)
+
+
+def pt_chunk_host_adamw_step(ctx, hp: pt_hparams, first_chunk: int, n_chunks: int, h_grad, h_master, h_m, h_v,
+                             h_param16, n_threads: int, stream=None):
+    _check(lib().pt_chunk_host_adamw_step(ctx, C.byref(hp), int(first_chunk), int(n_chunks), _ptr_array(h_grad),
+                                          _ptr_array(h_master), _ptr_array(h_m), _ptr_array(h_v),
+                                          _ptr_array(h_param16), int(n_threads), _stream(stream)),
+           "pt_chunk_host_adamw_step", ctx)

@@ -10,12 +10,13 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libptchunk.so")
 PROBE = os.path.join(HERE, "ptchunk_probe")
-SOURCES = ["pt_ctx.hip", "pt_norm.hip", "pt_pack.hip", "pt_adamw.hip", "pt_stream.hip"]
+SOURCES = ["pt_ctx.hip", "pt_norm.hip", "pt_pack.hip", "pt_adamw.hip", "pt_stream.hip", "pt_host.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off",                     # the fp32 sequence of the update is written out FMA by FMA
     "-fno-fast-math",
+    "-fno-math-errno",                       # lets the host-side update loop vectorise its sqrt
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,

@@ -228,6 +228,7 @@ int pt_prepare_consts(pt_ctx* ctx, const pt_hparams* hp, hipStream_t stream) {
   }
   hipLaunchKernelGGL(k_prepare, dim3(1), dim3(1), 0, stream, ctx->d_state, *hp);
   PT_LAUNCH_CHECK(ctx, "k_prepare");
+  PT_HIP(ctx, hipEventRecord(ctx->ev_scalar, stream));   // lets the host-side update read the scalars early
   ctx->prepared = true;
   ctx->prepared_hp = *hp;
   return PT_OK;

@@ -114,6 +114,11 @@ struct pt_ctx {
   bool stream_pending = false;
   uint32_t last_slot = 0;
 
+  // host-side update: a side stream and a pinned landing buffer for the step's scalars
+  hipStream_t s_scalar = nullptr;
+  hipEvent_t ev_scalar = nullptr;
+  PtDevState* h_state = nullptr;
+
   std::string err;
 };
 

@@ -98,6 +98,9 @@ static void ctx_free_all(pt_ctx* ctx) {
     if (ctx->ev_down[s]) (void)hipEventDestroy(ctx->ev_down[s]);
     if (ctx->slot_mem[s]) (void)hipFree(ctx->slot_mem[s]);
   }
+  if (ctx->s_scalar) (void)hipStreamDestroy(ctx->s_scalar);
+  if (ctx->ev_scalar) (void)hipEventDestroy(ctx->ev_scalar);
+  if (ctx->h_state) (void)hipHostFree(ctx->h_state);
   if (ctx->d_state) (void)hipFree(ctx->d_state);
   if (ctx->d_table) (void)hipFree(ctx->d_table);
   if (ctx->d_chunk_sq) (void)hipFree(ctx->d_chunk_sq);
@@ -120,6 +123,9 @@ static int ctx_alloc(pt_ctx* ctx, const pt_scaler_cfg* sc) {
   size_t np = size_t(ctx->C) * ctx->norm_blocks;
   PT_HIP(ctx, hipMalloc(&ctx->d_norm_part, np * sizeof(double)));
   PT_HIP(ctx, hipMalloc(&ctx->d_norm_flag, np * sizeof(uint32_t)));
+  PT_HIP(ctx, hipStreamCreateWithFlags(&ctx->s_scalar, hipStreamNonBlocking));
+  PT_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_scalar, hipEventDisableTiming));
+  PT_HIP(ctx, hipHostMalloc((void**)&ctx->h_state, sizeof(PtDevState), hipHostMallocDefault));
   double init = sc ? sc->init_scale : 1.0;
   hipLaunchKernelGGL(k_init_state, dim3(1), dim3(1), 0, nullptr, ctx->d_state, init,
                      sc ? sc->growth : 1.0, sc ? sc->backoff : 1.0,

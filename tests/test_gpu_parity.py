@@ -322,14 +322,15 @@ def test_loss_scale_growth_on_device(orc):
 
 # ------------------------------------------------------------------- streamed == resident
 
-def run_mixed(sizes, S, n_persist, n_slots, steps, dtype=torch.bfloat16, scaler=None, inf_step=None):
+def run_mixed(sizes, S, n_persist, n_slots, steps, dtype=torch.bfloat16, scaler=None, inf_step=None, host_update=False):
     st = ChunkedState(sizes, S, dtype=dtype, scaler=scaler)
     try:
         hp_b, _, _ = hp_pair()
         C = st.C
         host = {}
         if n_persist < C:
-            B.pt_stream_reserve(st.ctx, n_slots)
+            if not host_update:
+                B.pt_stream_reserve(st.ctx, n_slots)
             for name, arena in (("g16", st.g16), ("p16", st.p16), ("w", st.w), ("m", st.m), ("v", st.v)):
                 host[name] = [torch.empty(S, dtype=arena.dtype).pin_memory() for _ in range(n_persist, C)]
             for name, arena in (("p16", st.p16), ("w", st.w), ("m", st.m), ("v", st.v)):
@@ -346,11 +347,14 @@ def run_mixed(sizes, S, n_persist, n_slots, steps, dtype=torch.bfloat16, scaler=
                 host["g16"][i].copy_(st.g16[c])
             torch.cuda.synchronize()
             st.norm()
-            if n_persist < C:
+            if n_persist < C and not host_update:
                 B.pt_chunk_stream_step(st.ctx, hp_b, n_persist, C - n_persist, host["g16"], host["w"], host["m"],
                                        host["v"], host["p16"])
             if n_persist > 0:
                 st.adamw(hp_b, 0, n_persist)
+            if n_persist < C and host_update:          # host threads work while the GPU kernel runs
+                B.pt_chunk_host_adamw_step(st.ctx, hp_b, n_persist, C - n_persist, host["g16"], host["w"], host["m"],
+                                           host["v"], host["p16"], 5)
             st.end()
         torch.cuda.synchronize()
         out = {}
@@ -376,6 +380,14 @@ def test_streamed_chunks_give_the_same_bits_as_resident_ones(dtype, scaler, inf_
             assert torch.equal(got[name].view(torch.int16 if got[name].element_size() == 2 else torch.int32),
                                ref[name].view(torch.int16 if ref[name].element_size() == 2 else torch.int32)), \
                 (name, n_persist, n_slots)
+        assert got["report"].step == ref["report"].step and got["report"].loss_scale == ref["report"].loss_scale
+    # the paper's placement: non-persistent chunks updated by host threads, same bits again
+    for n_persist in (3, 0, 5):
+        got = run_mixed(sizes, S, n_persist, 2, steps=3, dtype=dtype, scaler=scaler, inf_step=inf_step, host_update=True)
+        for name in ("p16", "w", "m", "v"):
+            assert torch.equal(got[name].view(torch.int16 if got[name].element_size() == 2 else torch.int32),
+                               ref[name].view(torch.int16 if ref[name].element_size() == 2 else torch.int32)), \
+                ("host", name, n_persist)
         assert got["report"].step == ref["report"].step and got["report"].loss_scale == ref["report"].loss_scale
 
 
