@@ -73,7 +73,10 @@ int main(int argc, char** argv) {
   std::vector<float*> w(C), m(C), v(C);
   for (uint32_t c = 0; c < C; ++c) {
     char* q;
-    CHECK_HIP(hipMalloc((void**)&q, 2 * S + extra)); src[c] = q;
+    // PROBE_SRC_SHIFT=<elements>: gradient tensors start that many elements into their allocation
+    // (1..7 makes source and chunk incongruent modulo 16 bytes)
+    const size_t src_shift = getenv("PROBE_SRC_SHIFT") ? 2 * (strtoull(getenv("PROBE_SRC_SHIFT"), nullptr, 10) & 7) : 0;
+    CHECK_HIP(hipMalloc((void**)&q, 2 * S + extra + 16)); src[c] = q + src_shift;
     CHECK_HIP(hipMalloc((void**)&q, 2 * S + extra)); g[c] = q + 1 * skew;
     CHECK_HIP(hipMalloc((void**)&q, 2 * S + extra)); p[c] = q + 2 * skew;
     CHECK_HIP(hipMalloc((void**)&q, 4 * S + extra)); w[c] = (float*)(q + 3 * skew);

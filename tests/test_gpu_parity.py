@@ -519,3 +519,51 @@ def test_grouped_layout_pack_and_step_against_oracle(orc, separate_allocs):
         torch.cuda.synchronize()
         B.pt_pack_plan_destroy(plan)
         B.pt_ctx_destroy(ctx)
+
+
+# ----------------------------------------------------- the step is capturable in a HIP graph
+
+def test_whole_step_replays_from_a_hip_graph_bit_for_bit():
+    """The hot calls neither allocate nor synchronise once the pointer tables are bound, so a
+    step can be captured and replayed; every replay matches the eager path bit for bit, with
+    eager work and synchronisations between replays."""
+    sizes, S = [300_000, 4099, 65_536], 1 << 16
+    a = ChunkedState(sizes, S)                 # eager
+    b = ChunkedState(sizes, S)                 # captured
+    try:
+        hp_b, _, _ = hp_pair()
+        side = torch.cuda.Stream()
+
+        def step_on(st, stream):
+            B.pt_chunk_pack_grads(st.ctx, st.plan, st.rows(st.g16), stream)
+            B.pt_chunk_grad_sqnorm(st.ctx, None, 0, st.C, True, stream)
+            B.pt_chunk_adamw_step(st.ctx, hp_b, 0, st.C, st.rows(st.g16), st.rows(st.w), st.rows(st.m), st.rows(st.v),
+                                  st.rows(st.p16), stream)
+            B.pt_step_end(st.ctx, stream)
+
+        for st in (a, b):
+            st.set_grads(1)
+        torch.cuda.synchronize()
+        step_on(a, torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step_on(b, side)                   # binds the pointer tables outside the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step_on(b, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        # the capture itself did not run anything: b is still one step behind nothing, same as a
+        for s in (2, 3, 4, 5):
+            for st in (a, b):
+                st.set_grads(s)
+            torch.cuda.synchronize()
+            step_on(a, torch.cuda.current_stream())
+            graph.replay()
+            torch.cuda.synchronize()
+            ha, hb = a.host_state(), b.host_state()
+            for name in ("g16", "w", "m", "v", "p16"):
+                assert_same_bits(hb[name], ha[name], (name, s))
+            ra, rb = a.report(), b.report()
+            assert (ra.step, ra.norm, ra.found_inf) == (rb.step, rb.norm, rb.found_inf) and ra.step == s
+    finally:
+        a.close(); b.close()
