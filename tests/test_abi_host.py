@@ -163,3 +163,14 @@ def test_llama7b_grouped_layout_keeps_every_block_whole():
     for b in range(32):
         assert len({place[t][0] for t, g in enumerate(gids) if g == b}) == 1
     assert waste < 0.03 * sum(sizes)
+
+
+def test_context_creation_without_a_gpu_is_an_error_code_not_a_crash():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present: creation succeeds here")
+    out = C.c_void_p()
+    assert B.lib().pt_ctx_create(C.byref(out), 0, 64, 1, None) == B.PT_ERR_HIP
+    assert not out.value and "hipGetDevice" in B.pt_last_error(None)
+    with pytest.raises(B.PtError):
+        B.pt_ctx_create(B.PT_BF16, 64, 1)
