@@ -197,6 +197,83 @@ def run_streamed(args) -> int:
                        "overlap_ratio_step_over_max": round(t_h / max(t_h_only, t_res), 4),
                        "ms_param16_upload_afterwards": round(1e3 * t_up, 2),
                        "speedup_of_streaming_through_the_gpu": round(t_h / t_step, 3)}
+    model = None
+    if args.model:
+        # ---- OPTIM-phase cost model: fit linear times on a few sizes, validate on held-out splits
+        plans_by_n = {n_persist: plan}
+
+        def plan_for(n):
+            if n not in plans_by_n:
+                plans_by_n[n] = B.pt_pack_plan_create(ctx, [s_ for s_ in res_segs if s_.chunk < n])
+            return plans_by_n[n]
+
+        def run(n_res, n_h, mode, k=3):
+            pl = plan_for(n_res) if n_res else None
+            def once():
+                if pl is not None:
+                    B.pt_chunk_pack_grads(ctx, pl, pack_rows, stream)
+                B.pt_chunk_grad_sqnorm(ctx, None, 0, C, True, stream)
+                if n_h and mode == B.PT_OPTIM_STREAM:
+                    B.pt_chunk_stream_step(ctx, hp, n_persist, n_h, h_g[:n_h], h_w[:n_h], h_m[:n_h], h_v[:n_h], h_p[:n_h], stream)
+                if n_res:
+                    B.pt_chunk_adamw_step(ctx, hp, 0, n_res, r_g[:n_res], r_w[:n_res], r_m[:n_res], r_v[:n_res], r_p[:n_res], stream)
+                if n_h and mode == B.PT_OPTIM_HOST:
+                    B.pt_chunk_host_adamw_step(ctx, hp, n_persist, n_h, h_g[:n_h], h_w[:n_h], h_m[:n_h], h_v[:n_h], h_p[:n_h],
+                                               host_threads, stream)
+                B.pt_step_end(ctx, stream)
+            once()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(k):
+                once()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t) / k
+
+        def fit(points):                 # least squares t = a + b * elems
+            xs = np.array([p_[0] for p_ in points], dtype=np.float64)
+            ys = np.array([p_[1] for p_ in points], dtype=np.float64)
+            b_, a_ = np.polyfit(xs, ys, 1)
+            return float(a_), float(b_)
+
+        hs = sorted({max(2, n_host // 8), max(3, n_host // 3), n_host})
+        gs = sorted({n_persist // 4, n_persist // 2, n_persist})
+        g_fix, g_per = fit([(n * S, run(n, 0, B.PT_OPTIM_HOST)) for n in gs])
+        l_fix, l_per = fit([(n * S, run(0, n, B.PT_OPTIM_STREAM, k=2)) for n in hs])
+        h_fix, h_per = fit([(n * S, run(0, n, B.PT_OPTIM_HOST)) for n in hs])
+        tg_, tl_ = g_fix + g_per * n_persist * S, l_fix + l_per * hs[1] * S
+        t_mix = run(n_persist, hs[1], B.PT_OPTIM_STREAM, k=2)
+        cont = max(0.0, (t_mix - max(tg_, tl_)) / min(tg_, tl_))
+        rates = B.pt_optim_rates(g_fix, g_per, l_fix, l_per, h_fix, h_per, cont)
+        held_out = [(n_persist // 2, n_host // 2, B.PT_OPTIM_STREAM), (n_persist, n_host, B.PT_OPTIM_STREAM),
+                    (3 * n_persist // 4, n_host // 4, B.PT_OPTIM_STREAM),
+                    (n_persist, n_host, B.PT_OPTIM_HOST), (n_persist // 2, n_host // 2, B.PT_OPTIM_HOST),
+                    (n_persist // 4, n_host, B.PT_OPTIM_HOST), (n_persist, max(2, n_host // 10), B.PT_OPTIM_HOST)]
+        rows_ = []
+        for n_res, n_h, mode in held_out:
+            meas = run(n_res, n_h, mode, k=2)
+            pred = B.pt_optim_predict(rates, S, n_res + n_h, n_res, mode)[2]
+            rows_.append({"n_persist": n_res, "n_other": n_h, "mode": "stream" if mode == B.PT_OPTIM_STREAM else "host",
+                          "measured_ms": round(1e3 * meas, 2), "predicted_ms": round(1e3 * pred, 2),
+                          "error_pct": round(100.0 * (pred - meas) / meas, 2)})
+            log(f"[model] {rows_[-1]}")
+        total = n_persist + n_host
+        choices = {}
+        for gb in (40, 80, 120, 200):
+            for mode, name in ((B.PT_OPTIM_STREAM, "stream"), (B.PT_OPTIM_HOST, "host")):
+                try:
+                    ch = B.pt_optim_choose(rates, S, total, gb * 10**9, mode, args.slots)
+                    choices[f"{gb}GB_{name}"] = {"n_persist": ch.n_persist, "n_slots": ch.n_slots,
+                                                  "predicted_ms": round(1e3 * ch.t_step, 2), "hbm_GB": round(ch.hbm_bytes / 1e9, 1)}
+                except B.PtError:
+                    choices[f"{gb}GB_{name}"] = None
+        model = {"rates": {"gpu_s_fixed": g_fix, "gpu_s_per_elem": g_per, "link_s_fixed": l_fix, "link_s_per_elem": l_per,
+                           "host_s_fixed": h_fix, "host_s_per_elem": h_per, "stream_contention": round(cont, 3)},
+                 "fit_sizes_chunks": {"gpu": gs, "other": hs}, "held_out": rows_,
+                 "max_abs_error_pct": max(abs(r_["error_pct"]) for r_ in rows_),
+                 "chooser_for_%d_chunks" % total: choices}
+        for n, pl in plans_by_n.items():
+            if n != n_persist:
+                B.pt_pack_plan_destroy(pl)
     rep = B.pt_step_report_read(ctx, stream)
     link_bytes = 14 * S * n_host
     per_dir = link_bytes / t_step / 1e9
@@ -217,6 +294,8 @@ def run_streamed(args) -> int:
     }
     if host_update:
         out["host_side_update"] = host_update
+    if model:
+        out["optim_model"] = model
     B.pt_pack_plan_destroy(plan)
     B.pt_ctx_destroy(ctx)
     print(json.dumps(out), flush=True)
@@ -279,6 +358,8 @@ def main() -> int:
     ap.add_argument("--slots", type=int, default=3, help="--stream: device chunk buffers")
     ap.add_argument("--host-update", action="store_true",
                     help="--stream: also time the paper's placement, host chunks updated by host threads")
+    ap.add_argument("--model", action="store_true",
+                    help="--stream: fit the OPTIM-phase cost model on this box and validate it on held-out splits")
     ap.add_argument("--host-threads", type=int, default=0, help="--host-update: threads (default: all cores)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:

@@ -287,6 +287,42 @@ int pt_update_consts_read(pt_ctx* ctx, pt_update_consts* out, void* stream);
  * skips if found_inf != 0.  For kernel-isolated tests. */
 int pt_step_override(pt_ctx* ctx, float grad_mult, int32_t found_inf, void* stream);
 
+/* ---- OPTIM-phase cost model (host only) -------------------------------------------------
+ * The paper's runtime model restricted to the optimizer phase (Appendix A.1, Eq. 2: the part
+ * that runs on the GPU and the part that does not run side by side, the longer one decides;
+ * both are "modeled based on parameter size") and its model-state memory term (Appendix A.2:
+ * M_persist * n_persist + M_buffer * n_buffer, here 16 bytes per element each).  Times are
+ * linear in the number of elements, with coefficients the caller measured (bench.py --model):
+ *   resident part   t = gpu_s_fixed  + gpu_s_per_elem  * n_persist * chunk_elems      (pack + update)
+ *   streamed part   t = link_s_fixed + link_s_per_elem * rest                         (PT_OPTIM_STREAM)
+ *   host-side part  t = host_s_fixed + host_s_per_elem * rest                         (PT_OPTIM_HOST)
+ *   step            t = max(resident, other) [+ stream_contention * min(resident, other) when streaming:
+ *                       the slot kernels and DMA engines share HBM with the resident update]
+ * A part over zero elements costs nothing. */
+typedef enum { PT_OPTIM_STREAM = 0, PT_OPTIM_HOST = 1 } pt_optim_mode;
+typedef struct {
+  double gpu_s_fixed, gpu_s_per_elem;
+  double link_s_fixed, link_s_per_elem;
+  double host_s_fixed, host_s_per_elem;
+  double stream_contention;
+} pt_optim_rates;
+typedef struct {
+  uint32_t n_persist;  /* resident chunks: the first n_persist of the model (prefix rule)   */
+  uint32_t n_slots;    /* chunk buffers counted in hbm_bytes (0 when everything is resident) */
+  int32_t mode;
+  int32_t reserved;
+  double t_step, t_gpu, t_other; /* predicted seconds */
+  uint64_t hbm_bytes;  /* 16 * chunk_elems * (n_persist + n_slots)                           */
+} pt_optim_choice;
+
+int pt_optim_predict(const pt_optim_rates* rates, uint64_t chunk_elems, uint32_t n_chunks, uint32_t n_persist,
+                     int mode, double* t_gpu, double* t_other, double* t_step);
+/* Exhaustive scan of n_persist in [0, n_chunks] under 16*chunk_elems*(n_persist + buffers) <=
+ * hbm_budget_bytes; least predicted step time wins, ties go to the smaller footprint.
+ * PT_ERR_INVALID_ARG if not even the chunk buffers fit. */
+int pt_optim_choose(const pt_optim_rates* rates, uint64_t chunk_elems, uint32_t n_chunks,
+                    uint64_t hbm_budget_bytes, int mode, uint32_t n_slots, pt_optim_choice* out);
+
 /* ---- measurement aid ----------------------------------------------------------------
  * A plain device-to-device streaming copy of `bytes` bytes (16-byte aligned pointers
  * and size): the known-size kernel against which hardware traffic counters and the

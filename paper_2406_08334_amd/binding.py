@@ -22,6 +22,7 @@ EXPORTS = [
     "pt_chunk_grad_sqnorm", "pt_chunk_adamw_step", "pt_stream_reserve", "pt_chunk_stream_step", "pt_step_end",
     "pt_step_report_read", "pt_update_consts_read", "pt_step_override", "pt_calib_copy", "pt_ctx_set_option",
     "pt_layout_grouped", "pt_chunk_size_search", "pt_chunk_host_adamw_step",
+    "pt_optim_predict", "pt_optim_choose",
 ]
 
 
@@ -48,6 +49,20 @@ class pt_step_report(C.Structure):
 
 class pt_update_consts(C.Structure):
     _fields_ = [("c", C.c_float * 9), ("skip", C.c_int32)]
+
+
+class pt_optim_rates(C.Structure):
+    _fields_ = [("gpu_s_fixed", C.c_double), ("gpu_s_per_elem", C.c_double), ("link_s_fixed", C.c_double),
+                ("link_s_per_elem", C.c_double), ("host_s_fixed", C.c_double), ("host_s_per_elem", C.c_double),
+                ("stream_contention", C.c_double)]
+
+
+class pt_optim_choice(C.Structure):
+    _fields_ = [("n_persist", C.c_uint32), ("n_slots", C.c_uint32), ("mode", C.c_int32), ("reserved", C.c_int32),
+                ("t_step", C.c_double), ("t_gpu", C.c_double), ("t_other", C.c_double), ("hbm_bytes", C.c_uint64)]
+
+
+PT_OPTIM_STREAM, PT_OPTIM_HOST = 0, 1
 
 
 class PtError(RuntimeError):
@@ -99,6 +114,9 @@ def lib():
         L.pt_step_override.argtypes = [vp, C.c_float, i32, vp]
         L.pt_calib_copy.argtypes = [vp, vp, u64, vp]
         L.pt_ctx_set_option.argtypes = [vp, C.c_char_p, C.c_int64]
+        dp = C.POINTER(C.c_double)
+        L.pt_optim_predict.argtypes = [C.POINTER(pt_optim_rates), u64, u32, u32, C.c_int, dp, dp, dp]
+        L.pt_optim_choose.argtypes = [C.POINTER(pt_optim_rates), u64, u32, u64, C.c_int, u32, C.POINTER(pt_optim_choice)]
         L.pt_layout_grouped.argtypes = [C.POINTER(u64), C.POINTER(u32), u32, u64, C.POINTER(pt_segment), u32,
                                         C.POINTER(u32), C.POINTER(u32), C.POINTER(u64)]
         L.pt_chunk_size_search.argtypes = [C.POINTER(u64), C.POINTER(u32), u32, u64, u64, u64, C.POINTER(u64),
@@ -311,3 +329,19 @@ def pt_chunk_host_adamw_step(ctx, hp: pt_hparams, first_chunk: int, n_chunks: in
                                           _ptr_array(h_master), _ptr_array(h_m), _ptr_array(h_v),
                                           _ptr_array(h_param16), int(n_threads), _stream(stream)),
            "pt_chunk_host_adamw_step", ctx)
+
+
+def pt_optim_predict(rates: pt_optim_rates, chunk_elems: int, n_chunks: int, n_persist: int, mode: int):
+    """-> (t_gpu, t_other, t_step) in seconds.  Host only."""
+    a, b, c = C.c_double(), C.c_double(), C.c_double()
+    _check(lib().pt_optim_predict(C.byref(rates), int(chunk_elems), int(n_chunks), int(n_persist), int(mode),
+                                  C.byref(a), C.byref(b), C.byref(c)), "pt_optim_predict")
+    return a.value, b.value, c.value
+
+
+def pt_optim_choose(rates: pt_optim_rates, chunk_elems: int, n_chunks: int, hbm_budget_bytes: int, mode: int,
+                    n_slots: int = 3) -> pt_optim_choice:
+    out = pt_optim_choice()
+    _check(lib().pt_optim_choose(C.byref(rates), int(chunk_elems), int(n_chunks), int(hbm_budget_bytes), int(mode),
+                                 int(n_slots), C.byref(out)), "pt_optim_choose")
+    return out
