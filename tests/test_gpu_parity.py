@@ -567,3 +567,74 @@ def test_whole_step_replays_from_a_hip_graph_bit_for_bit():
             assert (ra.step, ra.norm, ra.found_inf) == (rb.step, rb.norm, rb.found_inf) and ra.step == s
     finally:
         a.close(); b.close()
+
+
+# ------------------------------------------------------------- hyper-parameter corners, resume
+
+@pytest.mark.parametrize("kw", [dict(max_norm=0.0), dict(lr=0.0), dict(beta1=0.0, beta2=0.0), dict(weight_decay=0.0),
+                                dict(eps=1e-3, max_norm=1e9), dict(lr=3e-2, beta1=0.5, beta2=0.999, weight_decay=1.0)])
+def test_hyper_parameter_corners_end_to_end(orc, kw):
+    st = ChunkedState([70_000, 33, 8_200], 1 << 15)
+    try:
+        hp_b, hp_o, hpd = hp_pair(**kw)
+        host = st.host_state()
+        fa = {k: a.copy() for k, a in host.items()}
+        ost = orc.new_state(None)
+        trk = ScaleTracker(host["w"], host["m"], hpd)
+        for s in (1, 2, 3):
+            st.set_grads(s, std=1e-2)
+            st.pack(); st.norm(); st.adamw(hp_b)
+            rep = B.pt_step_report_read(st.ctx)
+            k = B.pt_update_consts_read(st.ctx)
+            st.end()
+            g16 = to_u16(st.g16).reshape(-1).copy()
+            orep = orc.step(hp_o, None, ost, g16, host["w"], host["m"], host["v"], host["p16"], st.S, orc.BF16, threads=4)
+            assert abs(rep.clip_coef - orep.clip_coef) <= 1e-12 * orep.clip_coef
+            if hpd["max_norm"] <= 0 or hpd["max_norm"] > 1e6:
+                assert rep.clip_coef == 1.0 and rep.grad_mult == 1.0
+            got = st.host_state()
+            trk.advance(s, orc.decode16(g16, orc.BF16).astype(np.float64) * orep.grad_mult, host["v"])
+            trk.check((got["w"], got["m"], got["v"]), (host["w"], host["m"], host["v"]), tol=1e-6)
+            fa["g16"] = g16
+            run_oracle_f32seq(orc, np.array(list(k.c), dtype=np.float32), fa, orc.BF16)
+            for name in ("w", "m", "v", "p16"):
+                assert_same_bits(got[name], fa[name], (name, s, kw))
+    finally:
+        st.close()
+
+
+def test_resume_from_saved_state_gives_the_same_bits():
+    sizes, S = [50_000, 4_100], 1 << 14
+    sb = B.pt_scaler_cfg(1024.0, 2.0, 0.5, 2, 0)              # grows every 2 good steps: the state matters
+    a = ChunkedState(sizes, S, dtype=torch.float16, scaler=sb)
+    b = None
+    try:
+        hp_b, _, _ = hp_pair()
+        scale = 1024.0
+        for s in (1, 2, 3):
+            a.set_grads(s, scale=scale)
+            a.step(hp_b)
+            scale = a.report().loss_scale
+        r = a.report()
+        assert (r.step, r.loss_scale, r.good_steps) == (3, 2048.0, 1)
+        snap = {k: getattr(a, k).clone() for k in ("p16", "w", "m", "v")}
+        # a fresh context resumed from the saved arrays and the three saved scalars
+        b = ChunkedState(sizes, S, dtype=torch.float16, scaler=sb, init_params=False)
+        for k, t in snap.items():
+            getattr(b, k).copy_(t)
+        B.pt_ctx_set_state(b.ctx, r.step, r.loss_scale, r.good_steps)
+        for s in (4, 5, 6):
+            for st in (a, b):
+                st.set_grads(s, scale=scale)
+                st.step(hp_b)
+            assert a.report().loss_scale == b.report().loss_scale
+            scale = a.report().loss_scale
+        ha, hb = a.host_state(), b.host_state()
+        for name in ("w", "m", "v", "p16"):
+            assert_same_bits(hb[name], ha[name], name)
+        ra, rb = a.report(), b.report()
+        assert (ra.step, ra.loss_scale, ra.good_steps) == (rb.step, rb.loss_scale, rb.good_steps) == (6, 8192.0, 0)
+    finally:
+        a.close()
+        if b is not None:
+            b.close()
