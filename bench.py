@@ -364,7 +364,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
-              "run it with --gpus 1. How the path would shard is described in DESIGN.md.", file=sys.stderr)
+              "run it with --gpus 1.", file=sys.stderr)
         return 2
     if args.stream:
         return run_streamed(args)

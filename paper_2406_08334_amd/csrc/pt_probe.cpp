@@ -47,8 +47,9 @@ int main(int argc, char** argv) {
   const int copies = argc > 4 ? atoi(argv[4]) : 4;
   printf("probe: %u chunks of %llu elements, %d steps, %d copies\n", C, (unsigned long long)S, steps, copies);
 
+  const uint32_t n_host = getenv("PROBE_STREAM_CHUNKS") ? (uint32_t)atoi(getenv("PROBE_STREAM_CHUNKS")) : 0;
   pt_ctx* ctx = nullptr;
-  CHECK_PT(nullptr, pt_ctx_create(&ctx, PT_BF16, S, C, nullptr));
+  CHECK_PT(nullptr, pt_ctx_create(&ctx, PT_BF16, S, C + n_host, nullptr));
 
   // one chunk of pseudo-random host data (LCG -> roughly uniform in +-1e-3 / +-0.03), replicated
   std::vector<uint16_t> hg(S), hp(S);
@@ -89,6 +90,7 @@ int main(int argc, char** argv) {
     CHECK_HIP(hipMemset(v[c], 0, 4 * S));
     CHECK_HIP(hipMemset(g[c], 0, 2 * S));
   }
+  g.resize(C + n_host, nullptr);   // pack takes one entry per chunk of the context; host chunks have none
   // one "tensor" per chunk, filling it completely
   std::vector<pt_segment> segs(C);
   for (uint32_t c = 0; c < C; ++c) segs[c] = pt_segment{src[c], 0, S, 0, c, c};
@@ -120,6 +122,37 @@ int main(int argc, char** argv) {
     const double n = double(S) * C;
     printf("step %d: pack %.3f ms (%.0f GB/s)  finalize %.3f ms  adamw %.3f ms (%.0f GB/s)  norm %.6f step %d\n", s,
            t_pack, 4.0 * n / t_pack / 1e6, t_norm, t_adamw, 28.0 * n / t_adamw / 1e6, rep.norm, rep.step);
+  }
+  // PROBE_STREAM_CHUNKS=<n> [PROBE_SLOTS=3]: n more chunks live in pinned host memory and go through
+  // pt_chunk_stream_step while the resident chunks update (needs a context of C + n chunks: see main's top)
+  if (n_host > 0) {
+    std::vector<void*> hgp(n_host), hpp(n_host);
+    std::vector<float*> hwp(n_host), hmp(n_host), hvp(n_host);
+    for (uint32_t i = 0; i < n_host; ++i) {
+      CHECK_HIP(hipHostMalloc(&hgp[i], 2 * S, hipHostMallocDefault));
+      CHECK_HIP(hipHostMalloc(&hpp[i], 2 * S, hipHostMallocDefault));
+      CHECK_HIP(hipHostMalloc((void**)&hwp[i], 4 * S, hipHostMallocDefault));
+      CHECK_HIP(hipHostMalloc((void**)&hmp[i], 4 * S, hipHostMallocDefault));
+      CHECK_HIP(hipHostMalloc((void**)&hvp[i], 4 * S, hipHostMallocDefault));
+      memcpy(hgp[i], hg.data(), 2 * S); memcpy(hpp[i], hp.data(), 2 * S); memcpy(hwp[i], hw.data(), 4 * S);
+      memset(hmp[i], 0, 4 * S); memset(hvp[i], 0, 4 * S);
+    }
+    const uint32_t slots = getenv("PROBE_SLOTS") ? (uint32_t)atoi(getenv("PROBE_SLOTS")) : 3;
+    CHECK_PT(ctx, pt_stream_reserve(ctx, slots));
+    for (int s = 0; s < steps; ++s) {
+      CHECK_HIP(hipEventRecord(e[0], st));
+      CHECK_PT(ctx, pt_chunk_pack_grads(ctx, plan, g.data(), st));
+      CHECK_PT(ctx, pt_chunk_grad_sqnorm(ctx, nullptr, 0, C, 1, st));
+      CHECK_PT(ctx, pt_chunk_stream_step(ctx, &hpar, C, n_host, hgp.data(), hwp.data(), hmp.data(), hvp.data(), hpp.data(), st));
+      CHECK_PT(ctx, pt_chunk_adamw_step(ctx, &hpar, 0, C, g.data(), w.data(), m.data(), v.data(), p.data(), st));
+      CHECK_PT(ctx, pt_step_end(ctx, st));
+      CHECK_HIP(hipEventRecord(e[1], st));
+      CHECK_HIP(hipStreamSynchronize(st));
+      float t;
+      CHECK_HIP(hipEventElapsedTime(&t, e[0], e[1]));
+      printf("streamed step %d: %u resident + %u host chunks, %u slots: %.2f ms, %.2f GB/s per direction\n", s, C, n_host, slots, t,
+             14.0 * double(S) * n_host / t / 1e6);
+    }
   }
   // PROBE_PACK_TILES="8192,16384,...": times pack with plans of each tile size, same process
   if (const char* tl = getenv("PROBE_PACK_TILES")) {
