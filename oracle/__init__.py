@@ -77,16 +77,17 @@ def lib():
         L.orc_clip_coef.restype = C.c_double
         L.orc_clip_coef.argtypes = [C.c_double, C.c_double]
         L.orc_adamw_f64.restype = None
+        u8p = C.POINTER(C.c_uint8)
         L.orc_adamw_f64.argtypes = [C.POINTER(Hparams), C.c_int32, C.c_double, u16p, f32p, f32p, f32p,
-                                    u16p, C.c_uint64, C.c_int, C.c_int]
+                                    u16p, C.c_uint64, C.c_int, C.c_int, u8p]
         L.orc_consts_f32.restype = None
         L.orc_consts_f32.argtypes = [C.POINTER(Hparams), C.c_int32, C.c_double, f32p]
         L.orc_adamw_f32seq.restype = None
-        L.orc_adamw_f32seq.argtypes = [f32p, u16p, f32p, f32p, f32p, u16p, C.c_uint64, C.c_int, C.c_int]
+        L.orc_adamw_f32seq.argtypes = [f32p, u16p, f32p, f32p, f32p, u16p, C.c_uint64, C.c_int, C.c_int, u8p]
         L.orc_step.restype = None
         L.orc_step.argtypes = [C.POINTER(Hparams), C.POINTER(ScalerCfg), C.POINTER(State), u16p, f32p,
                                f32p, f32p, u16p, C.c_uint64, C.c_uint64, C.c_int, C.c_int, C.c_int,
-                               C.POINTER(Report)]
+                               C.POINTER(Report), u8p]
         L.orc_hardware_threads.restype = C.c_int
         L.orc_hardware_threads.argtypes = []
         _lib = L
@@ -170,33 +171,42 @@ def consts_f32(hp: Hparams, t: int, grad_mult: float) -> np.ndarray:
     return c
 
 
-def adamw_f64(hp: Hparams, t: int, grad_mult: float, g16, w, m, v, p16, dtype: int, threads: int = 1):
-    """In-place fp64-evaluated AdamW on flat arrays (w, m, v float32; g16, p16 uint16)."""
+def _u8_or_null(a, n):
+    if a is None:
+        return None
+    assert isinstance(a, np.ndarray) and a.dtype == np.uint8 and a.flags.c_contiguous and a.size == n
+    return a.ctypes.data_as(C.POINTER(C.c_uint8))
+
+
+def adamw_f64(hp: Hparams, t: int, grad_mult: float, g16, w, m, v, p16, dtype: int, threads: int = 1,
+              no_decay=None):
+    """In-place fp64-evaluated AdamW on flat arrays (w, m, v float32; g16, p16 uint16).
+    no_decay: optional uint8 array, non-zero = that element is not decayed."""
     n = w.size
     assert g16.size == n and m.size == n and v.size == n and p16.size == n
     lib().orc_adamw_f64(C.byref(hp), int(t), float(grad_mult), _u16(g16), _f32(w), _f32(m), _f32(v),
-                        _u16(p16), n, dtype, int(threads))
+                        _u16(p16), n, dtype, int(threads), _u8_or_null(no_decay, n))
 
 
-def adamw_f32seq(consts: np.ndarray, g16, w, m, v, p16, dtype: int, threads: int = 1):
+def adamw_f32seq(consts: np.ndarray, g16, w, m, v, p16, dtype: int, threads: int = 1, no_decay=None):
     """In-place AdamW in the fp32 operation sequence, driven by the nine fp32 constants."""
     n = w.size
     assert g16.size == n and m.size == n and v.size == n and p16.size == n
     consts = np.ascontiguousarray(consts, dtype=np.float32)
     assert consts.size == 9
     lib().orc_adamw_f32seq(_f32(consts), _u16(g16), _f32(w), _f32(m), _f32(v), _u16(p16), n, dtype,
-                           int(threads))
+                           int(threads), _u8_or_null(no_decay, n))
 
 
 def step(hp: Hparams, sc: ScalerCfg | None, st: State, g16, w, m, v, p16, S: int, dtype: int,
-         use_f32seq: bool = False, threads: int = 1) -> Report:
+         use_f32seq: bool = False, threads: int = 1, no_decay=None) -> Report:
     """One whole optimizer step (scan, norm, clip, update or skip, loss-scale machine)."""
     n = w.size
     assert g16.size == n and m.size == n and v.size == n and p16.size == n
     rep = Report()
     lib().orc_step(C.byref(hp), C.byref(sc) if sc is not None else None, C.byref(st), _u16(g16),
                    _f32(w), _f32(m), _f32(v), _u16(p16), n, int(S), dtype, int(bool(use_f32seq)),
-                   int(threads), C.byref(rep))
+                   int(threads), C.byref(rep), _u8_or_null(no_decay, n))
     return rep
 
 

@@ -241,9 +241,12 @@ double orc_clip_coef(double norm, double max_norm) {
 // evaluated in fp64 from the fp32 state, each result rounded once to fp32 (the
 // state arrays ARE fp32: that rounding is part of the method, not of the oracle),
 // and p16 = RNE16(w').
+// no_decay (may be NULL): one byte per element; a non-zero byte switches the decay factor of
+// that element to 1 (weight-decay groups: biases and normalisation gains are commonly kept out
+// of the decay; the paper does not speak of weight decay at all).
 void orc_adamw_f64(const orc_hparams* hp, int32_t t, double grad_mult, const uint16_t* g16,
                    float* w, float* m, float* v, uint16_t* p16, uint64_t n, int dtype,
-                   int threads) {
+                   int threads, const uint8_t* no_decay) {
   const double b1 = hp->beta1, b2 = hp->beta2;
   const double bc1 = 1.0 - std::pow(b1, double(t));
   const double bc2 = 1.0 - std::pow(b2, double(t));
@@ -257,7 +260,7 @@ void orc_adamw_f64(const orc_hparams* hp, int32_t t, double grad_mult, const uin
       double mn = b1 * double(m[i]) + (1.0 - b1) * g;
       double vn = b2 * double(v[i]) + (1.0 - b2) * g * g;
       double denom = std::sqrt(vn) / sqrt_bc2 + eps;
-      double wn = double(w[i]) * decay - step_size * (mn / denom);
+      double wn = double(w[i]) * ((no_decay && no_decay[i]) ? 1.0 : decay) - step_size * (mn / denom);
       m[i] = float(mn);
       v[i] = float(vn);
       w[i] = float(wn);
@@ -286,7 +289,7 @@ void orc_consts_f32(const orc_hparams* hp, int32_t t, double grad_mult, float* c
 // fmaf is a single rounding).  A device kernel that performs the same correctly
 // rounded operations in the same order gives the same bits.
 void orc_adamw_f32seq(const float* c, const uint16_t* g16, float* w, float* m, float* v,
-                      uint16_t* p16, uint64_t n, int dtype, int threads) {
+                      uint16_t* p16, uint64_t n, int dtype, int threads, const uint8_t* no_decay) {
   const float b1 = c[0], b2 = c[1], omb1 = c[2], omb2 = c[3], decay = c[4], step_size = c[5],
               rsb2 = c[6], eps = c[7], gm = c[8];
   parallel_ranges(n, threads, [&](uint64_t lo, uint64_t hi) {
@@ -299,7 +302,7 @@ void orc_adamw_f32seq(const float* c, const uint16_t* g16, float* w, float* m, f
       float vn = std::fmaf(b2, v[i], t2);
       float d = std::fmaf(std::sqrt(vn), rsb2, eps);
       float u = mn / d;
-      float t3 = w[i] * decay;
+      float t3 = w[i] * ((no_decay && no_decay[i]) ? 1.0f : decay);
       float wn = std::fmaf(-step_size, u, t3);
       m[i] = mn;
       v[i] = vn;
@@ -317,7 +320,7 @@ void orc_adamw_f32seq(const float* c, const uint16_t* g16, float* w, float* m, f
 // clip, grad_mult) are always fp64.
 void orc_step(const orc_hparams* hp, const orc_scaler_cfg* sc, orc_state* st, const uint16_t* g16,
               float* w, float* m, float* v, uint16_t* p16, uint64_t n, uint64_t S, int dtype,
-              int use_f32seq, int threads, orc_report* rep) {
+              int use_f32seq, int threads, orc_report* rep, const uint8_t* no_decay) {
   const double sigma = st->loss_scale;
   rep->loss_scale_used = sigma;
   rep->found_inf = orc_found_nonfinite(g16, n, dtype);
@@ -338,9 +341,9 @@ void orc_step(const orc_hparams* hp, const orc_scaler_cfg* sc, orc_state* st, co
   if (use_f32seq) {
     float c[9];
     orc_consts_f32(hp, st->t, rep->grad_mult, c);
-    orc_adamw_f32seq(c, g16, w, m, v, p16, n, dtype, threads);
+    orc_adamw_f32seq(c, g16, w, m, v, p16, n, dtype, threads, no_decay);
   } else {
-    orc_adamw_f64(hp, st->t, rep->grad_mult, g16, w, m, v, p16, n, dtype, threads);
+    orc_adamw_f64(hp, st->t, rep->grad_mult, g16, w, m, v, p16, n, dtype, threads, no_decay);
   }
   if (sc && sc->enabled) {
     st->good_steps += 1;

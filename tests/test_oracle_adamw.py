@@ -326,3 +326,49 @@ def test_chunk_size_does_not_change_the_update(orc):
         r = orc.step(hp(), None, st, g16, *a, S, orc.BF16)
         outs.append((r.norm, a))
     assert abs(outs[0][0] - outs[2][0]) <= 1e-12 * outs[2][0]
+
+
+# ------------------------------------------------------------- weight-decay groups (no-decay mask)
+
+def test_no_decay_mask_closed_form_and_library_pin(orc):
+    n, S = 6000, 2048
+    g16, w, m, v, p16 = fresh(n, std_g=0.1)
+    mask = np.zeros(n, np.uint8)
+    mask[100:1100] = 1; mask[4000] = 1; mask[n - 7:] = 1
+    w0 = w.astype(np.float64)
+    g = orc.decode16(g16, orc.BF16).astype(np.float64) * 0.5
+    a = [x.copy() for x in (w, m, v, p16)]
+    orc.adamw_f64(hp(), 1, 0.5, g16, *a, orc.BF16, no_decay=mask)
+    # step 1 from zero state: decayed elements lose lr*wd*w, masked ones do not
+    want = w0 - 1e-4 * g / (np.abs(g) + 1e-8) - np.where(mask, 0.0, 1e-4 * 0.1 * w0)
+    assert np.all(np.abs(a[0] - want) <= 0.5 * ulp32(a[0]) * 1.0001 + 1e-17)
+    # the fp32 sequence with the mask stays at the fp64 evaluation; without a mask nothing changed
+    b = [x.copy() for x in (w, m, v, p16)]
+    orc.adamw_f32seq(orc.consts_f32(hp(), 1, 0.5), g16, *b, orc.BF16, no_decay=mask)
+    assert np.all(np.abs(b[0].astype(np.float64) - a[0]) <= 2e-7 * (np.abs(w0) + 1e-4))
+    c0 = [x.copy() for x in (w, m, v, p16)]; c1 = [x.copy() for x in (w, m, v, p16)]
+    orc.adamw_f64(hp(), 1, 0.5, g16, *c0, orc.BF16)
+    orc.adamw_f64(hp(), 1, 0.5, g16, *c1, orc.BF16, no_decay=np.zeros(n, np.uint8))
+    assert all(np.array_equal(x, y) for x, y in zip(c0, c1))
+    # library pin: torch.optim.AdamW with two parameter groups (wd 0.1 / wd 0), clipped together, fp64
+    steps = 3
+    gs16 = [synth.as_u16(synth.normal_16(synth.SEED_GRADS, s + 1, 0, 0, n, 0.1, torch.bfloat16, "cpu")).copy()
+            for s in range(steps)]
+    wa, ma, va, pa = w.copy(), m.copy(), v.copy(), p16.copy()
+    st = orc.new_state(None)
+    trk = ScaleTracker(w, m, HP)
+    for s in range(steps):
+        r = orc.step(hp(), None, st, gs16[s], wa, ma, va, pa, S, orc.BF16, threads=2, no_decay=mask)
+        trk.advance(s + 1, orc.decode16(gs16[s], orc.BF16).astype(np.float64) * r.grad_mult, va)
+    idx_d, idx_n = np.flatnonzero(mask == 0), np.flatnonzero(mask)
+    pd = torch.nn.Parameter(torch.tensor(w[idx_d], dtype=torch.float64))
+    pn = torch.nn.Parameter(torch.tensor(w[idx_n], dtype=torch.float64))
+    opt = torch.optim.AdamW([{"params": [pd], "weight_decay": 0.1}, {"params": [pn], "weight_decay": 0.0}],
+                            lr=1e-4, betas=(0.9, 0.95), eps=1e-8)
+    for s in range(steps):
+        gf = orc.decode16(gs16[s], orc.BF16).astype(np.float64)
+        pd.grad = torch.tensor(gf[idx_d]); pn.grad = torch.tensor(gf[idx_n])
+        torch.nn.utils.clip_grad_norm_([pd, pn], 1.0)
+        opt.step()
+    wt = np.empty(n); wt[idx_d] = pd.detach().numpy(); wt[idx_n] = pn.detach().numpy()
+    assert np.all(np.abs(wa - wt) <= 1e-6 * trk.W)
