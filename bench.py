@@ -316,6 +316,7 @@ def run_in_processes(args) -> int:
                "--cpu-sample-chunks", str(args.cpu_sample_chunks), "--layout", args.layout]
         if args.calib: cmd.append("--calib")
         if args.sweep: cmd.append("--sweep")
+        if args.no_decay_1d: cmd.append("--no-decay-1d")
         if args.no_cpu_baseline or i != args.processes - 1: cmd.append("--no-cpu-baseline")
         res = subprocess.run(cmd, stdout=subprocess.PIPE, text=True)
         if res.returncode != 0:
@@ -346,6 +347,8 @@ def main() -> int:
     ap.add_argument("--calib", action="store_true", help="also time a bare copy kernel (attainable HBM rate)")
     ap.add_argument("--layout", default="dense", choices=["dense", "grouped"],
                     help="dense: the benchmark configurations' layout; grouped: the paper's no-split, block-per-chunk layout")
+    ap.add_argument("--no-decay-1d", action="store_true",
+                    help="keep biases and normalisation gains out of the weight decay (masked update kernel)")
     ap.add_argument("--processes", type=int, default=2,
                     help="measure in this many fresh processes one after the other and report the best "
                          "(physical placement of the state differs from process to process)")
@@ -368,8 +371,8 @@ def main() -> int:
         return 2
     if args.stream:
         return run_streamed(args)
-    if args.layout == "grouped":
-        args.no_cpu_baseline = True      # the oracle leg samples the dense layout's first chunks
+    if args.layout == "grouped" or args.no_decay_1d:
+        args.no_cpu_baseline = True      # the oracle leg samples the dense layout's first chunks, all decayed
     if not args.child and args.processes > 1:
         return run_in_processes(args)
 
@@ -409,6 +412,11 @@ def main() -> int:
 
     t0 = time.time()
     ctx = B.pt_ctx_create(B.PT_BF16, S, C, None)
+    if args.no_decay_1d:
+        one_d = {i for i, (name, _) in enumerate(table) if name.endswith(".bias") or "norm" in name or ".ln_" in name}
+        nd = [B.pt_segment(0, 0, s.len, s.chunk_off, s.chunk, s.tensor) for s in segs if s.tensor in one_d]
+        B.pt_ctx_set_no_decay(ctx, nd)
+        layout_note += f"; {len(one_d)} one-dimensional tensors ({sum(s.len for s in nd)} elements) without weight decay"
     g16 = torch.zeros(C, S, dtype=torch.bfloat16, device=dev)
     p16 = torch.zeros(C, S, dtype=torch.bfloat16, device=dev)
     offs = np.cumsum([0] + sizes[:-1]).tolist()
@@ -507,7 +515,7 @@ def main() -> int:
         "kernels_ms": {"pack_grads+chunk_reduce": round(mean(pack_ms), 4), "finalize": round(mean(norm_ms), 4),
                        "adamw(+prepare)": round(mean(adamw_ms), 4)},
         "step_report": {"norm": rep.norm, "clip_coef": rep.clip_coef, "found_inf": rep.found_inf, "step": rep.step},
-        "roofline": {"kernel": "k_adamw<bf16, unroll 4, non-temporal>", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+        "roofline": {"kernel": "k_adamw<bf16, unroll 4, non-temporal%s>" % (", no-decay runs" if args.no_decay_1d else ""), "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": MEASURED_TRAFFIC.get(args.workload) if args.layout == "dense" else None,
                      "bytes_per_launch": adamw_bytes, "avg_launch_ms": round(mean(adamw_ms), 4)},

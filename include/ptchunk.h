@@ -125,6 +125,13 @@ int pt_ctx_destroy(pt_ctx* ctx);
 /* Overwrites the step counter / loss-scale state (resume).  Enqueued on stream. */
 int pt_ctx_set_state(pt_ctx* ctx, int32_t step, double loss_scale, int32_t good_steps, void* stream);
 
+/* Weight-decay groups.  The listed runs (chunk, chunk_off, len of each segment; src is ignored)
+ * are kept OUT of the weight decay in every later update of this context - resident, streamed
+ * or host-side: their decay factor is 1 instead of 1 - lr*wd (biases and normalisation gains in
+ * common practice; the paper does not speak of weight decay).  Replaces any earlier list;
+ * n_segs == 0 clears it.  Allocates and synchronises the device: an init-time call. */
+int pt_ctx_set_no_decay(pt_ctx* ctx, const pt_segment* segs, uint32_t n_segs);
+
 /* Launch-shape options (host state only, take effect at the next call; none of them
  * changes a result bit).
  *   "adamw_grid"    workgroups of the update kernel; 0 = the library's default

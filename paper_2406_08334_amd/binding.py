@@ -22,7 +22,7 @@ EXPORTS = [
     "pt_chunk_grad_sqnorm", "pt_chunk_adamw_step", "pt_stream_reserve", "pt_chunk_stream_step", "pt_step_end",
     "pt_step_report_read", "pt_update_consts_read", "pt_step_override", "pt_calib_copy", "pt_ctx_set_option",
     "pt_layout_grouped", "pt_chunk_size_search", "pt_chunk_host_adamw_step",
-    "pt_optim_predict", "pt_optim_choose",
+    "pt_optim_predict", "pt_optim_choose", "pt_ctx_set_no_decay",
 ]
 
 
@@ -114,6 +114,7 @@ def lib():
         L.pt_step_override.argtypes = [vp, C.c_float, i32, vp]
         L.pt_calib_copy.argtypes = [vp, vp, u64, vp]
         L.pt_ctx_set_option.argtypes = [vp, C.c_char_p, C.c_int64]
+        L.pt_ctx_set_no_decay.argtypes = [vp, C.POINTER(pt_segment), u32]
         dp = C.POINTER(C.c_double)
         L.pt_optim_predict.argtypes = [C.POINTER(pt_optim_rates), u64, u32, u32, C.c_int, dp, dp, dp]
         L.pt_optim_choose.argtypes = [C.POINTER(pt_optim_rates), u64, u32, u64, C.c_int, u32, C.POINTER(pt_optim_choice)]
@@ -345,3 +346,11 @@ def pt_optim_choose(rates: pt_optim_rates, chunk_elems: int, n_chunks: int, hbm_
     _check(lib().pt_optim_choose(C.byref(rates), int(chunk_elems), int(n_chunks), int(hbm_budget_bytes), int(mode),
                                  int(n_slots), C.byref(out)), "pt_optim_choose")
     return out
+
+
+def pt_ctx_set_no_decay(ctx, segments):
+    n = len(segments)
+    arr = (pt_segment * max(n, 1))()
+    for i, s in enumerate(segments):
+        arr[i] = s
+    _check(lib().pt_ctx_set_no_decay(ctx, arr, n), "pt_ctx_set_no_decay", ctx)

@@ -97,9 +97,10 @@ __device__ __forceinline__ uint32_t encode16(float x) {
 
 struct Consts { float b1, b2, omb1, omb2, decay, step_size, rsb2, eps, gm; };
 
+// dk: decay factor of each of the four elements (k.decay, or 1 for elements kept out of the decay)
 template <int DT>
-__device__ __forceinline__ void update_unit(const Consts& k, u32x2 g2, f32x4& w, f32x4& m, f32x4& v,
-                                            u32x2& p2) {
+__device__ __forceinline__ void update_unit(const Consts& k, const float (&dk)[4], u32x2 g2, f32x4& w, f32x4& m,
+                                            f32x4& v, u32x2& p2) {
   uint32_t gw[4] = {g2.x & 0xffffu, g2.x >> 16, g2.y & 0xffffu, g2.y >> 16};
   uint32_t pw[4];
 #pragma unroll
@@ -113,7 +114,7 @@ __device__ __forceinline__ void update_unit(const Consts& k, u32x2 g2, f32x4& w,
     float vn = __builtin_fmaf(k.b2, v[j], t2);
     float d = __builtin_fmaf(__builtin_sqrtf(vn), k.rsb2, k.eps);
     float u = mn / d;
-    float t3 = w[j] * k.decay;
+    float t3 = w[j] * dk[j];
     float wn = __builtin_fmaf(-k.step_size, u, t3);
     m[j] = mn; v[j] = vn; w[j] = wn;
     pw[j] = encode16<DT>(wn);
@@ -126,10 +127,16 @@ __device__ __forceinline__ void update_unit(const Consts& k, u32x2 g2, f32x4& w,
 // the launch: tile T belongs to chunk T / tiles_per_chunk.  Block b takes tiles
 // b, b + gridDim.x, ...  A block's consecutive tiles mostly stay in one chunk, so the
 // five base pointers are re-read from the table only when the chunk changes.
-template <int DT, int UNROLL, bool NT>
+//
+// MASKED: some element ranges of some chunks are kept out of the weight decay (sorted,
+// disjoint ranges per chunk: nd_begin[c] .. nd_begin[c+1] index pairs (lo, hi) in nd_ranges).
+// A tile that no range touches, or that lies inside one range, runs the same vector path with
+// one decay factor; only tiles cut by a range edge take the element-wise path.
+template <int DT, int UNROLL, bool NT, bool MASKED>
 __global__ void __launch_bounds__(AW_THREADS)
 k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_col, uint32_t n_cols,
-        uint64_t S, uint32_t tiles_per_chunk, const PtDevState* __restrict__ st, int recast_on_skip) {
+        uint64_t S, uint32_t tiles_per_chunk, const PtDevState* __restrict__ st, int recast_on_skip,
+        const uint32_t* __restrict__ nd_begin, const uint64_t* __restrict__ nd_ranges, uint32_t mask_chunk0) {
   constexpr uint32_t TILE_UNITS = AW_THREADS * UNROLL;
   const uint64_t units = S / 4;
   const uint32_t total_tiles = tiles_per_chunk * n_cols;
@@ -174,6 +181,44 @@ k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_
       pp = (gu32x2_ptr)(table[size_t(ROW_P16) * table_cols + col]);
     }
     const uint64_t u0 = uint64_t(tile) * TILE_UNITS + threadIdx.x;
+    float dtile = k.decay;            // decay factor of the whole tile, when it has one
+    bool cut = false;                 // a range edge falls inside this tile
+    uint32_t r0 = 0, r1 = 0;          // ranges of this chunk from the first one that ends after the tile start
+    if (MASKED) {
+      const uint32_t c = mask_chunk0 + ci;
+      r1 = nd_begin[c + 1];
+      uint32_t lo = nd_begin[c], hi = r1;
+      const uint64_t e0 = uint64_t(tile) * TILE_UNITS * 4, e1 = e0 + uint64_t(TILE_UNITS) * 4;
+      while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (nd_ranges[2 * size_t(mid) + 1] <= e0) lo = mid + 1; else hi = mid;
+      }
+      r0 = lo;
+      if (r0 < r1 && nd_ranges[2 * size_t(r0)] < e1) {
+        if (nd_ranges[2 * size_t(r0)] <= e0 && nd_ranges[2 * size_t(r0) + 1] >= e1) dtile = 1.0f;
+        else cut = true;
+      }
+    }
+    if (MASKED && cut) {
+      // element-wise decay factors; also covers a ragged last tile
+      const uint64_t u_end = min(units, (uint64_t(tile) + 1) * TILE_UNITS);
+      for (uint64_t u = u0; u < u_end; u += AW_THREADS) {
+        float dk[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint64_t e = 4 * u + j;
+          float d = k.decay;
+          for (uint32_t r = r0; r < r1 && nd_ranges[2 * size_t(r)] <= e; ++r)
+            if (e < nd_ranges[2 * size_t(r) + 1]) d = 1.0f;
+          dk[j] = d;
+        }
+        u32x2 g = gp[u]; f32x4 w = wp[u], m = mp[u], v = vp[u]; u32x2 p;
+        update_unit<DT>(k, dk, g, w, m, v, p);
+        wp[u] = w; mp[u] = m; vp[u] = v; pp[u] = p;
+      }
+      continue;
+    }
+    const float dk[4] = {dtile, dtile, dtile, dtile};
     if ((uint64_t(tile) + 1) * TILE_UNITS <= units) {
       u32x2 g[UNROLL]; f32x4 w[UNROLL], m[UNROLL], v[UNROLL];
 #pragma unroll
@@ -188,7 +233,7 @@ k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_
       for (int r = 0; r < UNROLL; ++r) {
         const uint64_t u = u0 + uint64_t(r) * AW_THREADS;
         u32x2 p;
-        update_unit<DT>(k, g[r], w[r], m[r], v[r], p);
+        update_unit<DT>(k, dk, g[r], w[r], m[r], v[r], p);
         st_stream<NT>(w[r], wp + u);
         st_stream<NT>(m[r], mp + u);
         st_stream<NT>(v[r], vp + u);
@@ -198,7 +243,7 @@ k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_
       // ragged last tile of a chunk
       for (uint64_t u = u0; u < units; u += AW_THREADS) {
         u32x2 g = gp[u]; f32x4 w = wp[u], m = mp[u], v = vp[u]; u32x2 p;
-        update_unit<DT>(k, g, w, m, v, p);
+        update_unit<DT>(k, dk, g, w, m, v, p);
         wp[u] = w; mp[u] = m; vp[u] = v; pp[u] = p;
       }
     }
@@ -206,15 +251,15 @@ k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_
 }
 
 typedef void (*adamw_kernel_t)(const uint64_t*, uint32_t, uint32_t, uint32_t, uint64_t, uint32_t,
-                               const PtDevState*, int);
+                               const PtDevState*, int, const uint32_t*, const uint64_t*, uint32_t);
 
-template <int DT>
+template <int DT, bool MASKED>
 adamw_kernel_t pick_kernel(uint32_t unroll, bool nt) {
   switch (unroll) {
-    case 1: return nt ? k_adamw<DT, 1, true> : k_adamw<DT, 1, false>;
-    case 2: return nt ? k_adamw<DT, 2, true> : k_adamw<DT, 2, false>;
-    case 8: return nt ? k_adamw<DT, 8, true> : k_adamw<DT, 8, false>;
-    default: return nt ? k_adamw<DT, 4, true> : k_adamw<DT, 4, false>;
+    case 1: return nt ? k_adamw<DT, 1, true, MASKED> : k_adamw<DT, 1, false, MASKED>;
+    case 2: return nt ? k_adamw<DT, 2, true, MASKED> : k_adamw<DT, 2, false, MASKED>;
+    case 8: return nt ? k_adamw<DT, 8, true, MASKED> : k_adamw<DT, 8, false, MASKED>;
+    default: return nt ? k_adamw<DT, 4, true, MASKED> : k_adamw<DT, 4, false, MASKED>;
   }
 }
 
@@ -234,7 +279,8 @@ int pt_prepare_consts(pt_ctx* ctx, const pt_hparams* hp, hipStream_t stream) {
   return PT_OK;
 }
 
-int pt_launch_adamw(pt_ctx* ctx, uint32_t first_col, uint32_t n_cols, hipStream_t stream, bool recast_on_skip) {
+int pt_launch_adamw(pt_ctx* ctx, uint32_t first_col, uint32_t n_cols, hipStream_t stream, bool recast_on_skip,
+                    uint32_t mask_chunk0) {
   if (n_cols == 0) return PT_OK;
   const uint32_t unroll = ctx->opt_adamw_unroll;
   const uint64_t units = ctx->S / 4;
@@ -248,10 +294,13 @@ int pt_launch_adamw(pt_ctx* ctx, uint32_t first_col, uint32_t n_cols, hipStream_
   uint32_t want = ctx->opt_adamw_grid > 0 ? ctx->opt_adamw_grid : (total + 2) / 3;
   if (ctx->opt_adamw_grid == 0 && want < PT_ADAMW_MIN_GRID) want = PT_ADAMW_MIN_GRID;
   dim3 grid(want < total ? want : total);
-  adamw_kernel_t kern = ctx->dtype == PT_BF16 ? pick_kernel<PT_BF16>(unroll, ctx->opt_adamw_nt != 0)
-                                              : pick_kernel<PT_FP16>(unroll, ctx->opt_adamw_nt != 0);
+  const bool nt = ctx->opt_adamw_nt != 0, masked = ctx->d_nd_begin != nullptr;
+  adamw_kernel_t kern = ctx->dtype == PT_BF16
+      ? (masked ? pick_kernel<PT_BF16, true>(unroll, nt) : pick_kernel<PT_BF16, false>(unroll, nt))
+      : (masked ? pick_kernel<PT_FP16, true>(unroll, nt) : pick_kernel<PT_FP16, false>(unroll, nt));
   hipLaunchKernelGGL(kern, grid, dim3(AW_THREADS), 0, stream, ctx->d_table, ctx->table_cols, first_col, n_cols,
-                     ctx->S, uint32_t(tpc), ctx->d_state, recast_on_skip ? 1 : 0);
+                     ctx->S, uint32_t(tpc), ctx->d_state, recast_on_skip ? 1 : 0, ctx->d_nd_begin, ctx->d_nd_ranges,
+                     mask_chunk0);
   PT_LAUNCH_CHECK(ctx, "k_adamw");
   return PT_OK;
 }
@@ -277,5 +326,5 @@ extern "C" int pt_chunk_adamw_step(pt_ctx* ctx, const pt_hparams* hp, uint32_t f
   if ((rc = pt_table_bind(ctx, ROW_V, first_chunk, n_chunks, (const void* const*)v, false, st, nullptr)) != PT_OK) return rc;
   if ((rc = pt_table_bind(ctx, ROW_P16, first_chunk, n_chunks, (const void* const*)param16, false, st, nullptr)) != PT_OK) return rc;
   if ((rc = pt_prepare_consts(ctx, hp, st)) != PT_OK) return rc;
-  return pt_launch_adamw(ctx, first_chunk, n_chunks, st, false);
+  return pt_launch_adamw(ctx, first_chunk, n_chunks, st, false, first_chunk);
 }

@@ -114,6 +114,12 @@ struct pt_ctx {
   bool stream_pending = false;
   uint32_t last_slot = 0;
 
+  // weight-decay groups: per chunk, sorted disjoint element ranges kept out of the decay
+  uint32_t* d_nd_begin = nullptr;        // [C + 1] indices into d_nd_ranges (NULL: no ranges set)
+  uint64_t* d_nd_ranges = nullptr;       // pairs (lo, hi)
+  std::vector<uint32_t> h_nd_begin;
+  std::vector<uint64_t> h_nd_ranges;
+
   // host-side update: a side stream and a pinned landing buffer for the step's scalars
   hipStream_t s_scalar = nullptr;
   hipEvent_t ev_scalar = nullptr;
@@ -157,7 +163,9 @@ inline const uint64_t* pt_row(const pt_ctx* ctx, int row) {
 // [first_col, first_col + n_cols).
 int pt_prepare_consts(pt_ctx* ctx, const pt_hparams* hp, hipStream_t stream);
 // recast_on_skip: on a skipped step rewrite param16 = RNE(master) instead of doing nothing.
-int pt_launch_adamw(pt_ctx* ctx, uint32_t first_col, uint32_t n_cols, hipStream_t stream, bool recast_on_skip);
+// mask_chunk0: chunk index (for the no-decay ranges) of table column first_col.
+int pt_launch_adamw(pt_ctx* ctx, uint32_t first_col, uint32_t n_cols, hipStream_t stream, bool recast_on_skip,
+                    uint32_t mask_chunk0);
 
 // ---- implemented in pt_norm.hip ---------------------------------------------------------
 // Sums per-block partials into per-chunk values.  uniform mode (tile_begin == NULL):

@@ -2,6 +2,8 @@
 // single-thread scalar kernels (state set / override / step end).
 #include "pt_common.h"
 
+#include <algorithm>
+
 #include <cstdlib>
 
 static thread_local std::string g_noctx_error;
@@ -101,6 +103,8 @@ static void ctx_free_all(pt_ctx* ctx) {
   if (ctx->s_scalar) (void)hipStreamDestroy(ctx->s_scalar);
   if (ctx->ev_scalar) (void)hipEventDestroy(ctx->ev_scalar);
   if (ctx->h_state) (void)hipHostFree(ctx->h_state);
+  if (ctx->d_nd_begin) (void)hipFree(ctx->d_nd_begin);
+  if (ctx->d_nd_ranges) (void)hipFree(ctx->d_nd_ranges);
   if (ctx->d_state) (void)hipFree(ctx->d_state);
   if (ctx->d_table) (void)hipFree(ctx->d_table);
   if (ctx->d_chunk_sq) (void)hipFree(ctx->d_chunk_sq);
@@ -218,6 +222,49 @@ extern "C" int pt_ctx_set_option(pt_ctx* ctx, const char* name, int64_t value) {
     return PT_OK;
   }
   return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_ctx_set_option: unknown option '%s'", name);
+}
+
+extern "C" int pt_ctx_set_no_decay(pt_ctx* ctx, const pt_segment* segs, uint32_t n_segs) {
+  if (!ctx) return PT_ERR_INVALID_ARG;
+  if (!segs && n_segs) return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_ctx_set_no_decay: segs is NULL");
+  // per chunk: sort, merge touching ranges
+  std::vector<std::vector<std::pair<uint64_t, uint64_t>>> per(ctx->C);
+  for (uint32_t i = 0; i < n_segs; ++i) {
+    const pt_segment& s = segs[i];
+    if (s.len == 0) continue;
+    if (s.chunk >= ctx->C || s.chunk_off >= ctx->S || s.len > ctx->S - s.chunk_off)
+      return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_ctx_set_no_decay: segment %u lies outside the context's chunks", i);
+    per[s.chunk].push_back({s.chunk_off, s.chunk_off + s.len});
+  }
+  std::vector<uint32_t> begin(size_t(ctx->C) + 1, 0);
+  std::vector<uint64_t> ranges;
+  for (uint32_t c = 0; c < ctx->C; ++c) {
+    auto& v = per[c];
+    std::sort(v.begin(), v.end());
+    size_t first = ranges.size() / 2;
+    for (auto& r : v) {
+      if (ranges.size() / 2 > first && r.first <= ranges.back()) {
+        if (r.second > ranges.back()) ranges.back() = r.second;
+      } else {
+        ranges.push_back(r.first);
+        ranges.push_back(r.second);
+      }
+    }
+    begin[c + 1] = uint32_t(ranges.size() / 2);
+  }
+  (void)hipDeviceSynchronize();          // kernels in flight may still read the old ranges
+  if (ctx->d_nd_begin) { (void)hipFree(ctx->d_nd_begin); ctx->d_nd_begin = nullptr; }
+  if (ctx->d_nd_ranges) { (void)hipFree(ctx->d_nd_ranges); ctx->d_nd_ranges = nullptr; }
+  ctx->h_nd_begin.clear();
+  ctx->h_nd_ranges.clear();
+  if (ranges.empty()) return PT_OK;      // nothing kept out of the decay: the unmasked kernel runs
+  PT_HIP(ctx, hipMalloc(&ctx->d_nd_ranges, ranges.size() * sizeof(uint64_t)));
+  PT_HIP(ctx, hipMemcpy(ctx->d_nd_ranges, ranges.data(), ranges.size() * sizeof(uint64_t), hipMemcpyHostToDevice));
+  PT_HIP(ctx, hipMalloc(&ctx->d_nd_begin, begin.size() * sizeof(uint32_t)));
+  PT_HIP(ctx, hipMemcpy(ctx->d_nd_begin, begin.data(), begin.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
+  ctx->h_nd_begin = std::move(begin);
+  ctx->h_nd_ranges = std::move(ranges);
+  return PT_OK;
 }
 
 extern "C" int pt_step_override(pt_ctx* ctx, float grad_mult, int32_t found_inf, void* stream) {

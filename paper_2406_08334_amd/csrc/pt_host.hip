@@ -10,6 +10,7 @@
 // compiler vectorises per x86 target (AVX-512 / AVX2 clones picked at load time).
 #include "pt_common.h"
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <thread>
@@ -125,6 +126,9 @@ extern "C" int pt_chunk_host_adamw_step(pt_ctx* ctx, const pt_hparams* hp, uint3
   const uint64_t total_grains = grains_per_chunk * n_chunks;
   std::atomic<uint64_t> next{0};
   const int dtype = ctx->dtype;
+  const bool masked = !ctx->h_nd_begin.empty();
+  const uint32_t* nd_begin = ctx->h_nd_begin.data();
+  const uint64_t* nd_ranges = ctx->h_nd_ranges.data();
   auto worker = [&]() {
     for (;;) {
       const uint64_t gidx = next.fetch_add(1, std::memory_order_relaxed);
@@ -133,8 +137,24 @@ extern "C" int pt_chunk_host_adamw_step(pt_ctx* ctx, const pt_hparams* hp, uint3
       const uint64_t n = (lo + HOST_GRAIN <= S) ? HOST_GRAIN : S - lo;
       const uint16_t* g = static_cast<const uint16_t*>(h_grad[c]) + lo;
       uint16_t* p = static_cast<uint16_t*>(h_param16[c]) + lo;
-      if (dtype == PT_BF16) host_update_bf16(k, g, h_master[c] + lo, h_m[c] + lo, h_v[c] + lo, p, n);
-      else host_update_fp16(k, g, h_master[c] + lo, h_m[c] + lo, h_v[c] + lo, p, n);
+      // runs of one decay factor: between and inside the chunk's no-decay ranges
+      uint64_t pos = lo;
+      const uint64_t end = lo + n;
+      uint32_t r = masked ? nd_begin[first_chunk + c] : 0;
+      const uint32_t r_end = masked ? nd_begin[first_chunk + c + 1] : 0;
+      while (r < r_end && nd_ranges[2 * size_t(r) + 1] <= pos) ++r;
+      while (pos < end) {
+        uint64_t stop = end;
+        HostConsts kk = k;
+        if (r < r_end && nd_ranges[2 * size_t(r)] < end) {
+          if (nd_ranges[2 * size_t(r)] > pos) stop = nd_ranges[2 * size_t(r)];          // decayed run up to the range
+          else { kk.decay = 1.0f; stop = std::min<uint64_t>(end, nd_ranges[2 * size_t(r) + 1]); ++r; }
+        }
+        const uint64_t off = pos - lo, cnt = stop - pos;
+        if (dtype == PT_BF16) host_update_bf16(kk, g + off, h_master[c] + pos, h_m[c] + pos, h_v[c] + pos, p + off, cnt);
+        else host_update_fp16(kk, g + off, h_master[c] + pos, h_m[c] + pos, h_v[c] + pos, p + off, cnt);
+        pos = stop;
+      }
     }
   };
   std::vector<std::thread> pool;

@@ -91,7 +91,7 @@ extern "C" int pt_chunk_stream_step(pt_ctx* ctx, const pt_hparams* hp, uint32_t 
     PT_HIP(ctx, hipEventRecord(ctx->ev_up[s], ctx->s_up));
     // update on the slot
     PT_HIP(ctx, hipStreamWaitEvent(ctx->s_comp, ctx->ev_up[s], 0));
-    if ((rc = pt_launch_adamw(ctx, ctx->C + s, 1, ctx->s_comp, true)) != PT_OK) return rc;
+    if ((rc = pt_launch_adamw(ctx, ctx->C + s, 1, ctx->s_comp, true, first_chunk + i)) != PT_OK) return rc;
     PT_HIP(ctx, hipEventRecord(ctx->ev_k[s], ctx->s_comp));
     // offload
     PT_HIP(ctx, hipStreamWaitEvent(ctx->s_down, ctx->ev_k[s], 0));

@@ -93,6 +93,17 @@ class ChunkedState:
     def report(self):
         return B.pt_step_report_read(self.ctx)
 
+    def set_no_decay(self, tensors=(), runs=()):
+        """Keeps whole tensors (by index) and/or raw (chunk, chunk_off, len) runs out of the weight
+        decay; returns the same choice as a flat uint8 mask over [C * S] for the oracle."""
+        segs = [B.pt_segment(0, 0, s.len, s.chunk_off, s.chunk, s.tensor) for s in self.segs if s.tensor in set(tensors)]
+        segs += [B.pt_segment(0, 0, n, off, c, 0) for c, off, n in runs]
+        B.pt_ctx_set_no_decay(self.ctx, segs)
+        mask = np.zeros(self.C * self.S, dtype=np.uint8)
+        for s in segs:
+            mask[s.chunk * self.S + s.chunk_off: s.chunk * self.S + s.chunk_off + s.len] = 1
+        return mask
+
     # ---- host copies for the oracle
     def host_state(self):
         torch.cuda.synchronize()

@@ -150,8 +150,9 @@ def test_nonfinite_is_found_wherever_it_sits(orc, dtype, pats):
 
 # ------------------------------------------------------------------------------- AdamW
 
-def run_oracle_f32seq(orc, consts, st_host, dtype):
-    orc.adamw_f32seq(consts, st_host["g16"], st_host["w"], st_host["m"], st_host["v"], st_host["p16"], dtype, threads=8)
+def run_oracle_f32seq(orc, consts, st_host, dtype, no_decay=None):
+    orc.adamw_f32seq(consts, st_host["g16"], st_host["w"], st_host["m"], st_host["v"], st_host["p16"], dtype, threads=8,
+                     no_decay=no_decay)
 
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
@@ -222,10 +223,11 @@ def test_adamw_golden_tiny_case(orc):
 
 
 def end_to_end(orc, sizes, S, dtype, steps, grad_std=1e-3, scaler_b=None, scaler_o=None, inf_step=None,
-               outlier_every=0, recompute_norm=False):
+               outlier_every=0, recompute_norm=False, no_decay_tensors=None):
     st = ChunkedState(sizes, S, dtype=dtype, scaler=scaler_b)
     try:
         hp_b, hp_o, hpd = hp_pair()
+        mask = st.set_no_decay(tensors=no_decay_tensors) if no_decay_tensors is not None else None
         host = st.host_state()
         ost = orc.new_state(scaler_o)
         trk = ScaleTracker(host["w"], host["m"], hpd)
@@ -245,7 +247,7 @@ def end_to_end(orc, sizes, S, dtype, steps, grad_std=1e-3, scaler_b=None, scaler
             st.end()
             g16 = to_u16(st.g16).reshape(-1).copy()
             orep = orc.step(hp_o, scaler_o, ost, g16, host["w"], host["m"], host["v"], host["p16"], S,
-                            st.orc_dtype, threads=8)
+                            st.orc_dtype, threads=8, no_decay=mask)
             reports.append((rep, orep))
             assert rep.found_inf == orep.found_inf
             assert rep.loss_scale == orep.loss_scale_used
@@ -268,7 +270,7 @@ def end_to_end(orc, sizes, S, dtype, steps, grad_std=1e-3, scaler_b=None, scaler
             assert far <= 1e-4 * got["p16"].size          # beyond one ulp only where w's terms cancel
             consts = np.array(list(k.c), dtype=np.float32)
             fa["g16"] = g16
-            run_oracle_f32seq(orc, consts, fa, st.orc_dtype)
+            run_oracle_f32seq(orc, consts, fa, st.orc_dtype, no_decay=mask)
             for name in ("w", "m", "v", "p16"):
                 assert_same_bits(got[name], fa[name], (name, s))
         return reports
@@ -322,10 +324,13 @@ def test_loss_scale_growth_on_device(orc):
 
 # ------------------------------------------------------------------- streamed == resident
 
-def run_mixed(sizes, S, n_persist, n_slots, steps, dtype=torch.bfloat16, scaler=None, inf_step=None, host_update=False):
+def run_mixed(sizes, S, n_persist, n_slots, steps, dtype=torch.bfloat16, scaler=None, inf_step=None, host_update=False,
+              no_decay_runs=None):
     st = ChunkedState(sizes, S, dtype=dtype, scaler=scaler)
     try:
         hp_b, _, _ = hp_pair()
+        if no_decay_runs is not None:
+            st.set_no_decay(runs=no_decay_runs)
         C = st.C
         host = {}
         if n_persist < C:
