@@ -1,5 +1,6 @@
-"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
-(all chunks of the state resident, one AdamW launch over the whole pointer table).
+"""GPU parity at the benchmark's full sizes, in the launch configurations bench.py times
+(all chunks of the state resident, one AdamW launch over the whole pointer table; and the
+split state: a resident prefix next to chunks that live in pinned host memory).
 
 The oracle cannot walk 6.7e9 elements several times in a test, so: pack is checked on
 every element through the layout's defining property (dense layout = flat concatenation),
@@ -73,18 +74,112 @@ class FullState:
                                             range(16)))
         return total, found
 
+    def run_step(self, hp_b):
+        """pack -> norm -> update of every chunk, as the benchmark enqueues it"""
+        C = self.C
+        B.pt_chunk_pack_grads(self.ctx, self.plan, self.rows(self.g16))
+        B.pt_chunk_grad_sqnorm(self.ctx, None, 0, C, True)
+        B.pt_chunk_adamw_step(self.ctx, hp_b, 0, C, self.rows(self.g16), self.rows(self.w), self.rows(self.m),
+                              self.rows(self.v), self.rows(self.p16))
+
+    def check_pack(self):
+        """every element: the dense layout is the flat concatenation, padding stays zero"""
+        N = self.N
+        assert torch.equal(self.g16.view(-1)[:N].view(torch.int16), self.grad_src.view(torch.int16))
+        assert not bool(self.g16.view(-1)[N:].view(torch.int16).any())
+
+    def check_padding(self):
+        """padding of the last chunk stayed exactly zero through every step"""
+        C, S = self.C, self.S
+        pad = C * S - self.N
+        if pad:
+            for a in (self.w, self.m, self.v):
+                assert not bool(a[C - 1][S - pad:].any())
+            assert not bool(self.p16[C - 1][S - pad:].view(torch.int16).any())
+
     def close(self):
         torch.cuda.synchronize()
         B.pt_pack_plan_destroy(self.plan)
         B.pt_ctx_destroy(self.ctx)
-        for name in ("grad_src", "g16", "p16", "w", "m", "v"):
+        for name in ("grad_src", "g16", "p16", "w", "m", "v", "host", "_pin"):
             setattr(self, name, None)
         gc.collect()
         torch.cuda.empty_cache()
 
 
-def run_full(workload, dtype, steps, scaler_b=None, scaler_o=None, inf_step=None, outlier_every=0, sample=None):
-    st = FullState(workload, dtype, scaler_b)
+class SplitState(FullState):
+    """The first n_resident + n_host chunks of a workload's dense layout: the prefix lives in HBM,
+    the rest in pinned host memory and takes the streamed update.  Gradient chunks are packed on
+    the device (where their norm partials are taken) and the host chunks' gradients offloaded."""
+
+    def __init__(self, workload, dtype, n_resident, n_host, n_slots=3):
+        table, S = shapes.workload(workload)
+        self.sizes = [n for _, n in table]
+        self.S, self.dtype = S, dtype
+        self.pt_dtype = B.PT_BF16 if dtype == torch.bfloat16 else B.PT_FP16
+        self.orc_dtype = O.BF16 if dtype == torch.bfloat16 else O.FP16
+        segs, c_all = B.pt_layout_dense(self.sizes, S)
+        C = self.C = n_resident + n_host
+        assert C < c_all, "the cut must fall on a chunk boundary before the padded last chunk"
+        self.n_resident, self.n_host = n_resident, n_host
+        N = self.N = C * S
+        dev = "cuda"
+        self.segs = [s for s in segs if s.chunk < C]
+        self.ctx = B.pt_ctx_create(self.pt_dtype, S, C, None)
+        B.pt_stream_reserve(self.ctx, n_slots)
+        self.grad_src = torch.empty(N, dtype=dtype, device=dev)
+        offs = np.cumsum([0] + self.sizes[:-1]).tolist()
+        for s in self.segs:
+            s.src = self.grad_src.data_ptr() + 2 * offs[s.tensor]
+        self.plan = B.pt_pack_plan_create(self.ctx, self.segs)
+        self.g16 = torch.zeros(C, S, dtype=dtype, device=dev)
+        R = n_resident
+        self.p16 = torch.zeros(R, S, dtype=dtype, device=dev)
+        synth.normal_16(synth.SEED_PARAMS, 0, 0, 0, R * S, 0.02, dtype, dev, out=self.p16.view(-1))
+        self.w = torch.empty(R, S, dtype=torch.float32, device=dev)
+        for c in range(R):
+            self.w[c].copy_(self.p16[c])
+        self.m = torch.zeros(R, S, dtype=torch.float32, device=dev)
+        self.v = torch.zeros(R, S, dtype=torch.float32, device=dev)
+        self.host = {name: [torch.zeros(S, dtype=dt, pin_memory=True) for _ in range(n_host)]
+                     for name, dt in (("g16", dtype), ("p16", dtype), ("w", torch.float32), ("m", torch.float32),
+                                      ("v", torch.float32))}
+        tmp = torch.empty(S, dtype=dtype, device=dev)
+        for i in range(n_host):
+            synth.normal_16(synth.SEED_PARAMS, 0, 0, (R + i) * S, S, 0.02, dtype, dev, out=tmp)
+            self.host["p16"][i].copy_(tmp)
+            self.host["w"][i].copy_(tmp.float())
+        self.rows = lambda a, lo=0, hi=None: [a[c] for c in range(lo, a.shape[0] if hi is None else hi)]
+        torch.cuda.synchronize()
+
+    def chunk_host(self, c):
+        torch.cuda.synchronize()
+        R = self.n_resident
+        if c < R:
+            return dict(g16=to_u16(self.g16[c]).copy(), p16=to_u16(self.p16[c]).copy(), w=self.w[c].cpu().numpy().copy(),
+                        m=self.m[c].cpu().numpy().copy(), v=self.v[c].cpu().numpy().copy())
+        h = {name: self.host[name][c - R] for name in self.host}
+        return dict(g16=to_u16(h["g16"]).copy(), p16=to_u16(h["p16"]).copy(), w=h["w"].numpy().copy(),
+                    m=h["m"].numpy().copy(), v=h["v"].numpy().copy())
+
+    def run_step(self, hp_b):
+        R, C, h = self.n_resident, self.C, self.host
+        B.pt_chunk_pack_grads(self.ctx, self.plan, self.rows(self.g16))
+        for i in range(self.n_host):                                # the offload of the gradient chunks
+            h["g16"][i].copy_(self.g16[R + i], non_blocking=True)
+        torch.cuda.synchronize()
+        B.pt_chunk_grad_sqnorm(self.ctx, None, 0, C, True)
+        B.pt_chunk_stream_step(self.ctx, hp_b, R, C - R, h["g16"], h["w"], h["m"], h["v"], h["p16"])
+        B.pt_chunk_adamw_step(self.ctx, hp_b, 0, R, self.rows(self.g16, 0, R), self.rows(self.w), self.rows(self.m),
+                              self.rows(self.v), self.rows(self.p16))
+
+    def check_padding(self):
+        pass                                                         # the cut leaves whole chunks only
+
+
+def run_full(workload, dtype, steps, scaler_b=None, scaler_o=None, inf_step=None, outlier_every=0, sample=None,
+             make_state=None):
+    st = make_state() if make_state is not None else FullState(workload, dtype, scaler_b)
     try:
         hp_b, hp_o, hpd = hp_pair()
         C, S, N = st.C, st.S, st.N
@@ -106,17 +201,12 @@ def run_full(workload, dtype, steps, scaler_b=None, scaler_o=None, inf_step=None
                             outlier_every=outlier_every, out=st.grad_src)
             if inf_step == s:
                 st.grad_src.view(torch.int16)[inf_elem] = 0x7C00 if dtype == torch.float16 else 0x7F80
-            B.pt_chunk_pack_grads(st.ctx, st.plan, st.rows(st.g16))
-            B.pt_chunk_grad_sqnorm(st.ctx, None, 0, C, True)
-            B.pt_chunk_adamw_step(st.ctx, hp_b, 0, C, st.rows(st.g16), st.rows(st.w), st.rows(st.m), st.rows(st.v),
-                                  st.rows(st.p16))
+            st.run_step(hp_b)
             rep = B.pt_step_report_read(st.ctx)
             k = B.pt_update_consts_read(st.ctx)
             B.pt_step_end(st.ctx)
             torch.cuda.synchronize()
-            # pack, every element: the dense layout is the flat concatenation, padding stays zero
-            assert torch.equal(st.g16.view(-1)[:N].view(torch.int16), st.grad_src.view(torch.int16))
-            assert not bool(st.g16.view(-1)[N:].view(torch.int16).any())
+            st.check_pack()
             # norm, every element
             want_sq, want_inf = st.oracle_sqnorm(sigma)
             assert rep.found_inf == int(want_inf)
@@ -163,12 +253,7 @@ def run_full(workload, dtype, steps, scaler_b=None, scaler_o=None, inf_step=None
                                 sh["f64"]["w"], sh["trk"].W, dtype == torch.float16)
                 assert far <= 1e-4 * S
             out.append(rep)
-        # padding of the last chunk stayed exactly zero through every step
-        pad = C * S - N
-        if pad:
-            for a in (st.w, st.m, st.v):
-                assert not bool(a[C - 1][S - pad:].any())
-            assert not bool(st.p16[C - 1][S - pad:].view(torch.int16).any())
+        st.check_padding()
         return out
     finally:
         st.close()
@@ -192,3 +277,14 @@ def test_llama7b_fp16_loss_scaling_with_planted_inf():
     reps = run_full("llama_7b", torch.float16, steps=4, scaler_b=sb, scaler_o=so, inf_step=3, sample=[0])
     assert [r.found_inf for r in reps] == [0, 0, 1, 0]
     assert [r.loss_scale for r in reps] == [65536.0, 65536.0, 65536.0, 32768.0]
+
+
+def test_llama13b_half_resident_half_streamed_from_pinned_host_memory():
+    """The split configuration: 97 chunks (104 GB) resident; of the 97 host chunks as many as this
+    kind of box lets a process pin (it stops near 68 GB: 56 chunks = 60 GB are taken here).  Norm
+    over every element of all 153 chunks; update checked on resident and streamed chunks alike."""
+    n_res, n_host = 97, 56
+    reps = run_full("llama_13b", torch.bfloat16, steps=2, sample=[0, n_res - 1, n_res, n_res + n_host // 2, n_res + n_host - 1],
+                    make_state=lambda: SplitState("llama_13b", torch.bfloat16, n_res, n_host))
+    for r in reps:
+        assert abs(r.norm - 1e-3 * math.sqrt((n_res + n_host) * (1 << 26))) < 0.06
