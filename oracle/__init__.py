@@ -88,6 +88,21 @@ def lib():
         L.orc_step.argtypes = [C.POINTER(Hparams), C.POINTER(ScalerCfg), C.POINTER(State), u16p, f32p,
                                f32p, f32p, u16p, C.c_uint64, C.c_uint64, C.c_int, C.c_int, C.c_int,
                                C.POINTER(Report), u8p]
+        L.orc_accum_f32.restype = None
+        L.orc_accum_f32.argtypes = [u16p, C.c_uint64, C.c_int, C.c_int, f32p]
+        L.orc_found_nonfinite_f32.restype = C.c_int32
+        L.orc_found_nonfinite_f32.argtypes = [f32p, C.c_uint64]
+        L.orc_sqnorm_f32.restype = C.c_double
+        L.orc_sqnorm_f32.argtypes = [f32p, C.c_uint64, C.c_double, C.c_uint64, C.c_int]
+        L.orc_adamw_f64_g32.restype = None
+        L.orc_adamw_f64_g32.argtypes = [C.POINTER(Hparams), C.c_int32, C.c_double, f32p, f32p, f32p, f32p,
+                                        u16p, C.c_uint64, C.c_int, C.c_int, u8p]
+        L.orc_adamw_f32seq_g32.restype = None
+        L.orc_adamw_f32seq_g32.argtypes = [f32p, f32p, f32p, f32p, f32p, u16p, C.c_uint64, C.c_int, C.c_int, u8p]
+        L.orc_step_g32.restype = None
+        L.orc_step_g32.argtypes = [C.POINTER(Hparams), C.POINTER(ScalerCfg), C.POINTER(State), f32p, f32p,
+                                   f32p, f32p, u16p, C.c_uint64, C.c_uint64, C.c_int, C.c_int, C.c_int,
+                                   C.POINTER(Report), u8p]
         L.orc_hardware_threads.restype = C.c_int
         L.orc_hardware_threads.argtypes = []
         _lib = L
@@ -212,3 +227,48 @@ def step(hp: Hparams, sc: ScalerCfg | None, st: State, g16, w, m, v, p16, S: int
 
 def new_state(sc: ScalerCfg | None) -> State:
     return State(0, 0, float(sc.init_scale) if (sc is not None and sc.enabled) else 1.0)
+
+
+# ---- gradient accumulation in fp32 (micro-batches) ----------------------------------------
+
+def accum_f32(src16: np.ndarray, acc: np.ndarray, dtype: int, overwrite: bool = False):
+    """acc (float32, in place) = [acc +] decode(src16), element by element."""
+    src16 = np.ascontiguousarray(src16, dtype=np.uint16).reshape(-1)
+    assert acc.size == src16.size
+    lib().orc_accum_f32(_u16(src16), src16.size, dtype, int(bool(overwrite)), _f32(acc))
+
+
+def found_nonfinite_f32(g32: np.ndarray) -> bool:
+    return bool(lib().orc_found_nonfinite_f32(_f32(g32), g32.size))
+
+
+def sqnorm_f32(g32: np.ndarray, loss_scale: float = 1.0, block: int = 0, threads: int = 1) -> float:
+    return float(lib().orc_sqnorm_f32(_f32(g32), g32.size, float(loss_scale), int(block), int(threads)))
+
+
+def adamw_f64_g32(hp: Hparams, t: int, grad_mult: float, g32, w, m, v, p16, dtype: int, threads: int = 1,
+                  no_decay=None):
+    n = w.size
+    assert g32.size == n and m.size == n and v.size == n and p16.size == n
+    lib().orc_adamw_f64_g32(C.byref(hp), int(t), float(grad_mult), _f32(g32), _f32(w), _f32(m), _f32(v),
+                            _u16(p16), n, dtype, int(threads), _u8_or_null(no_decay, n))
+
+
+def adamw_f32seq_g32(consts: np.ndarray, g32, w, m, v, p16, dtype: int, threads: int = 1, no_decay=None):
+    n = w.size
+    assert g32.size == n and m.size == n and v.size == n and p16.size == n
+    consts = np.ascontiguousarray(consts, dtype=np.float32)
+    assert consts.size == 9
+    lib().orc_adamw_f32seq_g32(_f32(consts), _f32(g32), _f32(w), _f32(m), _f32(v), _u16(p16), n, dtype,
+                               int(threads), _u8_or_null(no_decay, n))
+
+
+def step_g32(hp: Hparams, sc: ScalerCfg | None, st: State, g32, w, m, v, p16, S: int, dtype: int,
+             use_f32seq: bool = False, threads: int = 1, no_decay=None) -> Report:
+    n = w.size
+    assert g32.size == n and m.size == n and v.size == n and p16.size == n
+    rep = Report()
+    lib().orc_step_g32(C.byref(hp), C.byref(sc) if sc is not None else None, C.byref(st), _f32(g32),
+                       _f32(w), _f32(m), _f32(v), _u16(p16), n, int(S), dtype, int(bool(use_f32seq)),
+                       int(threads), C.byref(rep), _u8_or_null(no_decay, n))
+    return rep

@@ -31,7 +31,10 @@
 // decimal evaluation and torch.optim.AdamW in fp64; pack vs per-element brute
 // force and the round-trip invariant; the loss-scale machine vs a replay without
 // the skipped step.  orc_adamw_f32seq (the fp32 operation sequence) is pinned only
-// through its distance to orc_adamw_f64.
+// through its distance to orc_adamw_f64.  The fp32 gradient-accumulation variant
+// (orc_accum_f32, orc_sqnorm_f32, orc_*_g32): numpy float32 addition and exact rationals,
+// math.fsum, bit-identity with the 16-bit-gradient functions on decoded words, a closed form
+// on gradients no 16-bit word holds, torch.optim.AdamW in fp64 on accumulated gradients.
 
 #include <algorithm>
 #include <cmath>
@@ -145,6 +148,68 @@ typedef struct {
   int32_t found_inf, t_after;
 } orc_report;
 
+}  // extern "C"
+
+namespace {
+
+// The gradient of element i comes from `grad_at(i)` (its exact value as a double): 16-bit
+// gradient chunks decode their word, fp32 accumulation chunks hand over the stored float.
+template <class G>
+void adamw_f64_any(const orc_hparams* hp, int32_t t, double grad_mult, G grad_at,
+                   float* w, float* m, float* v, uint16_t* p16, uint64_t n, int dtype,
+                   int threads, const uint8_t* no_decay) {
+  const double b1 = hp->beta1, b2 = hp->beta2;
+  const double bc1 = 1.0 - std::pow(b1, double(t));
+  const double bc2 = 1.0 - std::pow(b2, double(t));
+  const double step_size = hp->lr / bc1;
+  const double decay = 1.0 - hp->lr * hp->weight_decay;
+  const double sqrt_bc2 = std::sqrt(bc2);
+  const double eps = hp->eps;
+  parallel_ranges(n, threads, [&](uint64_t lo, uint64_t hi) {
+    for (uint64_t i = lo; i < hi; ++i) {
+      double g = grad_at(i) * grad_mult;
+      double mn = b1 * double(m[i]) + (1.0 - b1) * g;
+      double vn = b2 * double(v[i]) + (1.0 - b2) * g * g;
+      double denom = std::sqrt(vn) / sqrt_bc2 + eps;
+      double wn = double(w[i]) * ((no_decay && no_decay[i]) ? 1.0 : decay) - step_size * (mn / denom);
+      m[i] = float(mn);
+      v[i] = float(vn);
+      w[i] = float(wn);
+      p16[i] = encode16(w[i], dtype);
+    }
+  });
+}
+
+// The fp32 operation sequence of the update; `grad_at(i)` is the gradient as a binary32 value.
+template <class G>
+void adamw_f32seq_any(const float* c, G grad_at, float* w, float* m, float* v,
+                      uint16_t* p16, uint64_t n, int dtype, int threads, const uint8_t* no_decay) {
+  const float b1 = c[0], b2 = c[1], omb1 = c[2], omb2 = c[3], decay = c[4], step_size = c[5],
+              rsb2 = c[6], eps = c[7], gm = c[8];
+  parallel_ranges(n, threads, [&](uint64_t lo, uint64_t hi) {
+    for (uint64_t i = lo; i < hi; ++i) {
+      float g = grad_at(i) * gm;
+      float t1 = omb1 * g;
+      float mn = std::fmaf(b1, m[i], t1);
+      float t2 = omb2 * g;
+      t2 = t2 * g;
+      float vn = std::fmaf(b2, v[i], t2);
+      float d = std::fmaf(std::sqrt(vn), rsb2, eps);
+      float u = mn / d;
+      float t3 = w[i] * ((no_decay && no_decay[i]) ? 1.0f : decay);
+      float wn = std::fmaf(-step_size, u, t3);
+      m[i] = mn;
+      v[i] = vn;
+      w[i] = wn;
+      p16[i] = encode16(wn, dtype);
+    }
+  });
+}
+
+}  // namespace
+
+extern "C" {
+
 // ---- conversions -------------------------------------------------------------
 
 float orc_decode16(uint16_t w, int dtype) { return decode16(w, dtype); }
@@ -247,26 +312,8 @@ double orc_clip_coef(double norm, double max_norm) {
 void orc_adamw_f64(const orc_hparams* hp, int32_t t, double grad_mult, const uint16_t* g16,
                    float* w, float* m, float* v, uint16_t* p16, uint64_t n, int dtype,
                    int threads, const uint8_t* no_decay) {
-  const double b1 = hp->beta1, b2 = hp->beta2;
-  const double bc1 = 1.0 - std::pow(b1, double(t));
-  const double bc2 = 1.0 - std::pow(b2, double(t));
-  const double step_size = hp->lr / bc1;
-  const double decay = 1.0 - hp->lr * hp->weight_decay;
-  const double sqrt_bc2 = std::sqrt(bc2);
-  const double eps = hp->eps;
-  parallel_ranges(n, threads, [&](uint64_t lo, uint64_t hi) {
-    for (uint64_t i = lo; i < hi; ++i) {
-      double g = double(decode16(g16[i], dtype)) * grad_mult;
-      double mn = b1 * double(m[i]) + (1.0 - b1) * g;
-      double vn = b2 * double(v[i]) + (1.0 - b2) * g * g;
-      double denom = std::sqrt(vn) / sqrt_bc2 + eps;
-      double wn = double(w[i]) * ((no_decay && no_decay[i]) ? 1.0 : decay) - step_size * (mn / denom);
-      m[i] = float(mn);
-      v[i] = float(vn);
-      w[i] = float(wn);
-      p16[i] = encode16(w[i], dtype);
-    }
-  });
+  adamw_f64_any(hp, t, grad_mult, [=](uint64_t i) { return double(decode16(g16[i], dtype)); }, w, m, v, p16, n,
+                dtype, threads, no_decay);
 }
 
 // ---- AdamW, the fp32 operation sequence ---------------------------------------
@@ -290,26 +337,39 @@ void orc_consts_f32(const orc_hparams* hp, int32_t t, double grad_mult, float* c
 // rounded operations in the same order gives the same bits.
 void orc_adamw_f32seq(const float* c, const uint16_t* g16, float* w, float* m, float* v,
                       uint16_t* p16, uint64_t n, int dtype, int threads, const uint8_t* no_decay) {
-  const float b1 = c[0], b2 = c[1], omb1 = c[2], omb2 = c[3], decay = c[4], step_size = c[5],
-              rsb2 = c[6], eps = c[7], gm = c[8];
-  parallel_ranges(n, threads, [&](uint64_t lo, uint64_t hi) {
-    for (uint64_t i = lo; i < hi; ++i) {
-      float g = decode16(g16[i], dtype) * gm;
-      float t1 = omb1 * g;
-      float mn = std::fmaf(b1, m[i], t1);
-      float t2 = omb2 * g;
-      t2 = t2 * g;
-      float vn = std::fmaf(b2, v[i], t2);
-      float d = std::fmaf(std::sqrt(vn), rsb2, eps);
-      float u = mn / d;
-      float t3 = w[i] * ((no_decay && no_decay[i]) ? 1.0f : decay);
-      float wn = std::fmaf(-step_size, u, t3);
-      m[i] = mn;
-      v[i] = vn;
-      w[i] = wn;
-      p16[i] = encode16(wn, dtype);
+  adamw_f32seq_any(c, [=](uint64_t i) { return decode16(g16[i], dtype); }, w, m, v, p16, n, dtype, threads, no_decay);
+}
+
+// Scalars of a step from its squared norm and non-finite flag (rep->sqnorm, rep->found_inf set by
+// the caller).  Returns false for a skipped step: state untouched, the update counter does not
+// advance, the loss scale backs off.  Otherwise the counter advances and the update may run.
+static bool step_scalars(const orc_hparams* hp, const orc_scaler_cfg* sc, orc_state* st, orc_report* rep) {
+  const double sigma = st->loss_scale;
+  rep->norm = std::sqrt(rep->sqnorm);
+  rep->clip_coef = orc_clip_coef(rep->norm, hp->max_norm);
+  rep->grad_mult = rep->clip_coef / sigma;
+  if (rep->found_inf) {
+    if (sc && sc->enabled) {
+      st->loss_scale = std::max(sigma * sc->backoff, 1.0);
+      st->good_steps = 0;
     }
-  });
+    rep->t_after = st->t;
+    return false;
+  }
+  st->t += 1;
+  return true;
+}
+
+// After an applied update: the loss scale grows every growth_interval good steps in a row.
+static void step_grow(const orc_scaler_cfg* sc, orc_state* st, orc_report* rep) {
+  if (sc && sc->enabled) {
+    st->good_steps += 1;
+    if (st->good_steps >= sc->growth_interval) {
+      st->loss_scale = st->loss_scale * sc->growth;
+      st->good_steps = 0;
+    }
+  }
+  rep->t_after = st->t;
 }
 
 // ---- one whole optimizer step on flat arrays --------------------------------------
@@ -325,19 +385,7 @@ void orc_step(const orc_hparams* hp, const orc_scaler_cfg* sc, orc_state* st, co
   rep->loss_scale_used = sigma;
   rep->found_inf = orc_found_nonfinite(g16, n, dtype);
   rep->sqnorm = orc_sqnorm(g16, n, dtype, sigma, S, threads);
-  rep->norm = std::sqrt(rep->sqnorm);
-  rep->clip_coef = orc_clip_coef(rep->norm, hp->max_norm);
-  rep->grad_mult = rep->clip_coef / sigma;
-  if (rep->found_inf) {
-    // skipped step: state untouched, the update counter does not advance
-    if (sc && sc->enabled) {
-      st->loss_scale = std::max(sigma * sc->backoff, 1.0);
-      st->good_steps = 0;
-    }
-    rep->t_after = st->t;
-    return;
-  }
-  st->t += 1;
+  if (!step_scalars(hp, sc, st, rep)) return;
   if (use_f32seq) {
     float c[9];
     orc_consts_f32(hp, st->t, rep->grad_mult, c);
@@ -345,14 +393,79 @@ void orc_step(const orc_hparams* hp, const orc_scaler_cfg* sc, orc_state* st, co
   } else {
     orc_adamw_f64(hp, st->t, rep->grad_mult, g16, w, m, v, p16, n, dtype, threads, no_decay);
   }
-  if (sc && sc->enabled) {
-    st->good_steps += 1;
-    if (st->good_steps >= sc->growth_interval) {
-      st->loss_scale = sigma * sc->growth;
-      st->good_steps = 0;
-    }
+  step_grow(sc, st, rep);
+}
+
+// ---- gradient accumulation in fp32 (micro-batches) ----------------------------------
+// Not in the paper, whose gradients are the 16-bit array of the model state; a variant of the
+// same path: the 16-bit gradients of several micro-batches are summed into an fp32 array of
+// the same layout, and norm, clipping and update read that array.
+//   overwrite: acc[i] = decode(src[i])           (first micro-batch)
+//   else:      acc[i] = acc[i] + decode(src[i])  (one binary32 addition)
+void orc_accum_f32(const uint16_t* src, uint64_t n, int dtype, int overwrite, float* acc) {
+  for (uint64_t i = 0; i < n; ++i) {
+    float x = decode16(src[i], dtype);
+    acc[i] = overwrite ? x : acc[i] + x;
   }
-  rep->t_after = st->t;
+}
+
+int32_t orc_found_nonfinite_f32(const float* g, uint64_t n) {
+  for (uint64_t i = 0; i < n; ++i)
+    if (!std::isfinite(g[i])) return 1;
+  return 0;
+}
+
+// As orc_sqnorm, over binary32 gradients.
+double orc_sqnorm_f32(const float* g, uint64_t n, double loss_scale, uint64_t block, int threads) {
+  if (n == 0) return 0.0;
+  if (block == 0) block = n;
+  uint64_t nb = (n + block - 1) / block;
+  std::vector<double> part(nb, 0.0);
+  parallel_ranges(nb, threads, [&](uint64_t b0, uint64_t b1) {
+    for (uint64_t b = b0; b < b1; ++b) {
+      uint64_t lo = b * block, hi = std::min(n, lo + block);
+      double s = 0.0;
+      for (uint64_t i = lo; i < hi; ++i) {
+        double x = double(g[i]) / loss_scale;
+        s += x * x;
+      }
+      part[b] = s;
+    }
+  });
+  double total = 0.0;
+  for (uint64_t b = 0; b < nb; ++b) total += part[b];
+  return total;
+}
+
+void orc_adamw_f64_g32(const orc_hparams* hp, int32_t t, double grad_mult, const float* g32,
+                       float* w, float* m, float* v, uint16_t* p16, uint64_t n, int dtype,
+                       int threads, const uint8_t* no_decay) {
+  adamw_f64_any(hp, t, grad_mult, [=](uint64_t i) { return double(g32[i]); }, w, m, v, p16, n, dtype, threads,
+                no_decay);
+}
+
+void orc_adamw_f32seq_g32(const float* c, const float* g32, float* w, float* m, float* v,
+                          uint16_t* p16, uint64_t n, int dtype, int threads, const uint8_t* no_decay) {
+  adamw_f32seq_any(c, [=](uint64_t i) { return g32[i]; }, w, m, v, p16, n, dtype, threads, no_decay);
+}
+
+// orc_step over accumulated binary32 gradients (dtype is that of the 16-bit parameters).
+void orc_step_g32(const orc_hparams* hp, const orc_scaler_cfg* sc, orc_state* st, const float* g32,
+                  float* w, float* m, float* v, uint16_t* p16, uint64_t n, uint64_t S, int dtype,
+                  int use_f32seq, int threads, orc_report* rep, const uint8_t* no_decay) {
+  const double sigma = st->loss_scale;
+  rep->loss_scale_used = sigma;
+  rep->found_inf = orc_found_nonfinite_f32(g32, n);
+  rep->sqnorm = orc_sqnorm_f32(g32, n, sigma, S, threads);
+  if (!step_scalars(hp, sc, st, rep)) return;
+  if (use_f32seq) {
+    float c[9];
+    orc_consts_f32(hp, st->t, rep->grad_mult, c);
+    orc_adamw_f32seq_g32(c, g32, w, m, v, p16, n, dtype, threads, no_decay);
+  } else {
+    orc_adamw_f64_g32(hp, st->t, rep->grad_mult, g32, w, m, v, p16, n, dtype, threads, no_decay);
+  }
+  step_grow(sc, st, rep);
 }
 
 int orc_hardware_threads(void) {
