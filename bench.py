@@ -290,6 +290,7 @@ def run_streamed(args) -> int:
         "link_utilisation_vs_bare_bidirectional": round(per_dir / ref, 4),
         "ms_resident_only": round(1e3 * t_res, 2), "ms_streamed_only": round(1e3 * t_str, 2),
         "overlap_ratio_step_over_max": round(t_step / max(t_res, t_str), 4),
+        "fill_GBps": round(fill_bytes / (mean(pack_ms) * 1e-3) / 1e9, 1),
         "step_report": {"norm": rep.norm, "found_inf": rep.found_inf, "step": rep.step},
     }
     if host_update:
@@ -317,6 +318,9 @@ def run_in_processes(args) -> int:
         if args.calib: cmd.append("--calib")
         if args.sweep: cmd.append("--sweep")
         if args.no_decay_1d: cmd.append("--no-decay-1d")
+        if args.grad_accum: cmd += ["--grad-accum", str(args.grad_accum)]
+        if args.zero_grads: cmd.append("--zero-grads")
+        if args.pack_tile: cmd += ["--pack-tile", str(args.pack_tile)]
         if args.no_cpu_baseline or i != args.processes - 1: cmd.append("--no-cpu-baseline")
         res = subprocess.run(cmd, stdout=subprocess.PIPE, text=True)
         if res.returncode != 0:
@@ -349,6 +353,10 @@ def main() -> int:
                     help="dense: the benchmark configurations' layout; grouped: the paper's no-split, block-per-chunk layout")
     ap.add_argument("--no-decay-1d", action="store_true",
                     help="keep biases and normalisation gains out of the weight decay (masked update kernel)")
+    ap.add_argument("--grad-accum", type=int, default=0, metavar="K",
+                    help="variant: K micro-batches accumulated into fp32 gradient chunks per step (0 = the 16-bit pack path)")
+    ap.add_argument("--pack-tile", type=int, default=0, help="elements one workgroup of pack / accumulate moves (0 = default)")
+    ap.add_argument("--zero-grads", action="store_true", help="variant: the update zeroes the gradient chunks it has read")
     ap.add_argument("--processes", type=int, default=2,
                     help="measure in this many fresh processes one after the other and report the best "
                          "(physical placement of the state differs from process to process)")
@@ -371,7 +379,7 @@ def main() -> int:
         return 2
     if args.stream:
         return run_streamed(args)
-    if args.layout == "grouped" or args.no_decay_1d:
+    if args.layout == "grouped" or args.no_decay_1d or args.grad_accum or args.zero_grads:
         args.no_cpu_baseline = True      # the oracle leg samples the dense layout's first chunks, all decayed
     if not args.child and args.processes > 1:
         return run_in_processes(args)
@@ -417,7 +425,15 @@ def main() -> int:
         nd = [B.pt_segment(0, 0, s.len, s.chunk_off, s.chunk, s.tensor) for s in segs if s.tensor in one_d]
         B.pt_ctx_set_no_decay(ctx, nd)
         layout_note += f"; {len(one_d)} one-dimensional tensors ({sum(s.len for s in nd)} elements) without weight decay"
-    g16 = torch.zeros(C, S, dtype=torch.bfloat16, device=dev)
+    if args.pack_tile:
+        B.pt_ctx_set_option(ctx, "pack_tile_elems", args.pack_tile)
+    if args.grad_accum:
+        B.pt_ctx_set_option(ctx, "grad_fp32", 1)
+        layout_note += f"; {args.grad_accum} micro-batches per step accumulated into fp32 gradient chunks"
+    if args.zero_grads:
+        B.pt_ctx_set_option(ctx, "adamw_zero_grads", 1)
+        layout_note += "; gradients zeroed by the update"
+    g16 = torch.zeros(C, S, dtype=torch.float32 if args.grad_accum else torch.bfloat16, device=dev)
     p16 = torch.zeros(C, S, dtype=torch.bfloat16, device=dev)
     offs = np.cumsum([0] + sizes[:-1]).tolist()
     if args.layout == "grouped":
@@ -464,8 +480,14 @@ def main() -> int:
         cpu_in = dict(g=u16(g16[:n_cpu]), p=u16(p16[:n_cpu]), w=w[:n_cpu].cpu().numpy().reshape(-1).copy(),
                       src=[u16(grad_sets[0][:n_cpu * S])])
 
+    A = args.grad_accum
+
     def one_step(k, ev=None):
-        B.pt_chunk_pack_grads(ctx, plans[k % n_sets], r_g, stream)
+        if A:
+            for j in range(A):
+                B.pt_chunk_accum_grads(ctx, plans[(k * A + j) % n_sets], r_g, j == 0, j == A - 1, stream)
+        else:
+            B.pt_chunk_pack_grads(ctx, plans[k % n_sets], r_g, stream)
         if ev: ev[0].record(stream)
         B.pt_chunk_grad_sqnorm(ctx, None, 0, C, True, stream)
         if ev: ev[1].record(stream)
@@ -497,8 +519,12 @@ def main() -> int:
     if K >= 40:
         log("[bench] adamw ms, mean per tenth of the run: " +
             " ".join(f"{mean(adamw_ms[i * K // 10:(i + 1) * K // 10]):.2f}" for i in range(10)))
-    step_bytes = PACK_BYTES_PER_ELEM * N + ADAMW_BYTES_PER_ELEM * N_pad
-    adamw_bytes = ADAMW_BYTES_PER_ELEM * N_pad
+    g_bytes = 4 if A else 2
+    adamw_per_elem = ADAMW_BYTES_PER_ELEM + (g_bytes - 2) + (g_bytes if args.zero_grads else 0)
+    # accumulation: 2 B read + 4 B written for the first micro-batch, 2 + 4 read + 4 written for each further one
+    fill_bytes = (6 + 10 * (A - 1)) * N if A else PACK_BYTES_PER_ELEM * N
+    step_bytes = fill_bytes + adamw_per_elem * N_pad
+    adamw_bytes = adamw_per_elem * N_pad
     achieved = adamw_bytes / (mean(adamw_ms) * 1e-3) / 1e9
     value = step_bytes / (ms_step * 1e-3) / 1e9
 
@@ -512,12 +538,13 @@ def main() -> int:
                    "chunk_elems": S, "n_chunks": C, "elements": N, "padded_elements": N_pad,
                    "step_bytes": step_bytes, "grad_sets": n_sets},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
-        "kernels_ms": {"pack_grads+chunk_reduce": round(mean(pack_ms), 4), "finalize": round(mean(norm_ms), 4),
+        "kernels_ms": {("accum_grads x%d+chunk_reduce" % A if A else "pack_grads+chunk_reduce"): round(mean(pack_ms), 4), "finalize": round(mean(norm_ms), 4),
                        "adamw(+prepare)": round(mean(adamw_ms), 4)},
+        "fill_GBps": round(fill_bytes / (mean(pack_ms) * 1e-3) / 1e9, 1),
         "step_report": {"norm": rep.norm, "clip_coef": rep.clip_coef, "found_inf": rep.found_inf, "step": rep.step},
-        "roofline": {"kernel": "k_adamw<bf16, unroll 4, non-temporal%s>" % (", no-decay runs" if args.no_decay_1d else ""), "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+        "roofline": {"kernel": "k_adamw<bf16, unroll 4, non-temporal%s%s%s>" % (", no-decay runs" if args.no_decay_1d else "", ", fp32 gradients" if A else "", ", zeroing gradients" if args.zero_grads else ""), "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC.get(args.workload) if args.layout == "dense" else None,
+                     "traffic": MEASURED_TRAFFIC.get(args.workload) if args.layout == "dense" and not A and not args.zero_grads else None,
                      "bytes_per_launch": adamw_bytes, "avg_launch_ms": round(mean(adamw_ms), 4)},
     }
 

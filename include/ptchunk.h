@@ -132,12 +132,23 @@ int pt_ctx_set_state(pt_ctx* ctx, int32_t step, double loss_scale, int32_t good_
  * n_segs == 0 clears it.  Allocates and synchronises the device: an init-time call. */
 int pt_ctx_set_no_decay(pt_ctx* ctx, const pt_segment* segs, uint32_t n_segs);
 
-/* Launch-shape options (host state only, take effect at the next call; none of them
- * changes a result bit).
+/* Options (host state only, take effect at the next call).  Launch shape - none of these
+ * changes a result bit:
  *   "adamw_grid"    workgroups of the update kernel; 0 = the library's default
  *   "adamw_unroll"  4-element units a lane loads before it computes: 1, 2, 4 or 8
  *   "adamw_nt"      1 = non-temporal hints on the update's loads and stores (default), 0 = none
- *   "pack_tile_elems"  elements one workgroup of pack/unpack moves; read by pt_pack_plan_create */
+ *   "pack_tile_elems"  elements one workgroup of pack/unpack moves; read by pt_pack_plan_create
+ * Gradient storage (variants of the path; the paper's gradients are the 16-bit array):
+ *   "grad_fp32"     1 = the gradient chunks of this context hold fp32 (micro-batches accumulated
+ *                   by pt_chunk_accum_grads): every `grad` / `h_grad` argument of the norm, the
+ *                   resident, streamed and host-side update then points to chunk_elems floats,
+ *                   and pt_chunk_pack_grads is refused.  Choose before pt_stream_reserve (the
+ *                   chunk buffers grow to 18 bytes per element; PT_ERR_STATE afterwards) and
+ *                   before pt_pack_plan_create (plans are tiled for the kernel they feed).
+ *   "adamw_zero_grads"  1 = pt_chunk_adamw_step overwrites every gradient element it has read
+ *                   with zero (for callers whose backward pass adds into the chunks); not on a
+ *                   skipped step.  The streamed and host-side updates never write gradients:
+ *                   their host copies are overwritten by the next offload. */
 int pt_ctx_set_option(pt_ctx* ctx, const char* name, int64_t value);
 
 /* ---- layout (host, integer only) ---------------------------------------------------
@@ -195,6 +206,17 @@ int pt_pack_plan_destroy(pt_pack_plan* plan);
  * grad_chunks: host array of ctx.n_chunks device pointers (entries of chunks the
  * plan does not touch may be NULL). */
 int pt_chunk_pack_grads(pt_ctx* ctx, const pt_pack_plan* plan, void* const* grad_chunks, void* stream);
+
+/* Gradient accumulation over micro-batches (a variant; needs option "grad_fp32").  For every
+ * element of every segment of the plan: acc = decode(src word) if `overwrite` (first
+ * micro-batch), else acc = acc + decode(src word), one binary32 addition.  acc_chunks: host
+ * array of ctx.n_chunks device pointers to chunk_elems floats each (256-byte aligned; entries
+ * of chunks the plan does not touch may be NULL); elements no segment covers are not written.
+ * take_norm != 0 (the last micro-batch): as pt_chunk_pack_grads, leaves per chunk the fp64 sum of
+ * (acc/loss_scale)^2 and the non-finite flag of the ACCUMULATED values in the context, for
+ * pt_chunk_grad_sqnorm(..., NULL, ...); with take_norm == 0 the context keeps its old partials. */
+int pt_chunk_accum_grads(pt_ctx* ctx, const pt_pack_plan* plan, float* const* acc_chunks, int overwrite,
+                         int take_norm, void* stream);
 
 /* Inverse copy: chunk words -> the segments' tensors (e.g. updated 16-bit
  * parameters back to the model's tensors; round-trip tests).  The segments' src

@@ -22,7 +22,7 @@ EXPORTS = [
     "pt_chunk_grad_sqnorm", "pt_chunk_adamw_step", "pt_stream_reserve", "pt_chunk_stream_step", "pt_step_end",
     "pt_step_report_read", "pt_update_consts_read", "pt_step_override", "pt_calib_copy", "pt_ctx_set_option",
     "pt_layout_grouped", "pt_chunk_size_search", "pt_chunk_host_adamw_step",
-    "pt_optim_predict", "pt_optim_choose", "pt_ctx_set_no_decay",
+    "pt_optim_predict", "pt_optim_choose", "pt_ctx_set_no_decay", "pt_chunk_accum_grads",
 ]
 
 
@@ -103,6 +103,7 @@ def lib():
         L.pt_pack_plan_destroy.argtypes = [vp]
         L.pt_chunk_pack_grads.argtypes = [vp, vp, pp, vp]
         L.pt_chunk_unpack.argtypes = [vp, vp, pp, vp]
+        L.pt_chunk_accum_grads.argtypes = [vp, vp, pp, C.c_int, C.c_int, vp]
         L.pt_chunk_grad_sqnorm.argtypes = [vp, pp, u32, u32, C.c_int, vp]
         L.pt_chunk_adamw_step.argtypes = [vp, C.POINTER(pt_hparams), u32, u32, pp, pp, pp, pp, pp, vp]
         L.pt_stream_reserve.argtypes = [vp, u32]
@@ -354,3 +355,8 @@ def pt_ctx_set_no_decay(ctx, segments):
     for i, s in enumerate(segments):
         arr[i] = s
     _check(lib().pt_ctx_set_no_decay(ctx, arr, n), "pt_ctx_set_no_decay", ctx)
+
+
+def pt_chunk_accum_grads(ctx, plan, acc_chunks, overwrite, take_norm, stream=None):
+    _check(lib().pt_chunk_accum_grads(ctx, plan, _ptr_array(acc_chunks), int(bool(overwrite)), int(bool(take_norm)),
+                                      _stream(stream)), "pt_chunk_accum_grads", ctx)

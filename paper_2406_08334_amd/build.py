@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libptchunk.so")
 PROBE = os.path.join(HERE, "ptchunk_probe")
-SOURCES = ["pt_ctx.hip", "pt_norm.hip", "pt_pack.hip", "pt_adamw.hip", "pt_stream.hip", "pt_host.hip", "pt_model.hip"]
+SOURCES = ["pt_ctx.hip", "pt_norm.hip", "pt_pack.hip", "pt_accum.hip", "pt_adamw.hip", "pt_stream.hip", "pt_host.hip", "pt_model.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -2,7 +2,8 @@
 // range through the context's device pointer table.
 //
 // HBM-bound: per element 14 bytes read (g16, w, m, v) and 14 written (w, m, v,
-// p16).  Work unit = 4 consecutive elements per lane: one 16-byte access per fp32
+// p16); 16 read with fp32 gradient chunks, and 2 or 4 more written when the gradients are
+// zeroed on the way out.  Work unit = 4 consecutive elements per lane: one 16-byte access per fp32
 // array and one 8-byte access per 16-bit array, so that every wave instruction
 // touches one contiguous 1 KiB (fp32) or 512 B (16-bit) span.  UNROLL units per
 // lane are loaded before the first is used, to keep enough bytes in flight.
@@ -97,16 +98,33 @@ __device__ __forceinline__ uint32_t encode16(float x) {
 
 struct Consts { float b1, b2, omb1, omb2, decay, step_size, rsb2, eps, gm; };
 
+// Four gradient elements as they sit in a gradient chunk: four 16-bit words, or four floats
+// when the chunk accumulates micro-batches in fp32.
+template <bool GF32> struct GradUnit { typedef u32x2 vec; };
+template <> struct GradUnit<true> { typedef f32x4 vec; };
+
+template <int DT, bool GF32>
+__device__ __forceinline__ void decode_unit(const typename GradUnit<GF32>::vec& q, float (&g)[4]) {
+  if constexpr (GF32) {
+    g[0] = q[0]; g[1] = q[1]; g[2] = q[2]; g[3] = q[3];
+  } else {
+    g[0] = decode16<DT>(q.x & 0xffffu); g[1] = decode16<DT>(q.x >> 16);
+    g[2] = decode16<DT>(q.y & 0xffffu); g[3] = decode16<DT>(q.y >> 16);
+  }
+}
+
 // dk: decay factor of each of the four elements (k.decay, or 1 for elements kept out of the decay)
-template <int DT>
-__device__ __forceinline__ void update_unit(const Consts& k, const float (&dk)[4], u32x2 g2, f32x4& w, f32x4& m,
+template <int DT, bool GF32>
+__device__ __forceinline__ void update_unit(const Consts& k, const float (&dk)[4],
+                                            const typename GradUnit<GF32>::vec& gq, f32x4& w, f32x4& m,
                                             f32x4& v, u32x2& p2) {
-  uint32_t gw[4] = {g2.x & 0xffffu, g2.x >> 16, g2.y & 0xffffu, g2.y >> 16};
+  float gv[4];
+  decode_unit<DT, GF32>(gq, gv);
   uint32_t pw[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     // one correctly rounded binary32 operation per line; contraction is off for this file
-    float g = decode16<DT>(gw[j]) * k.gm;
+    float g = gv[j] * k.gm;
     float t1 = k.omb1 * g;
     float mn = __builtin_fmaf(k.b1, m[j], t1);
     float t2 = k.omb2 * g;
@@ -132,12 +150,20 @@ __device__ __forceinline__ void update_unit(const Consts& k, const float (&dk)[4
 // disjoint ranges per chunk: nd_begin[c] .. nd_begin[c+1] index pairs (lo, hi) in nd_ranges).
 // A tile that no range touches, or that lies inside one range, runs the same vector path with
 // one decay factor; only tiles cut by a range edge take the element-wise path.
-template <int DT, int UNROLL, bool NT, bool MASKED>
+//
+// GF32: the gradient chunks hold fp32 (accumulated micro-batches) instead of 16-bit words.
+// zero_grads: every gradient element is overwritten with zero once it has been read (for
+// callers whose backward pass adds into the chunk); not on a skipped step.
+template <int DT, int UNROLL, bool NT, bool MASKED, bool GF32>
 __global__ void __launch_bounds__(AW_THREADS)
 k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_col, uint32_t n_cols,
         uint64_t S, uint32_t tiles_per_chunk, const PtDevState* __restrict__ st, int recast_on_skip,
-        const uint32_t* __restrict__ nd_begin, const uint64_t* __restrict__ nd_ranges, uint32_t mask_chunk0) {
+        const uint32_t* __restrict__ nd_begin, const uint64_t* __restrict__ nd_ranges, uint32_t mask_chunk0,
+        int zero_grads) {
+  typedef typename GradUnit<GF32>::vec gvec;
+  typedef PT_GLOBAL gvec* g_ptr;
   constexpr uint32_t TILE_UNITS = AW_THREADS * UNROLL;
+  const gvec gzero = {};
   const uint64_t units = S / 4;
   const uint32_t total_tiles = tiles_per_chunk * n_cols;
   if (st->skip) {
@@ -166,7 +192,7 @@ k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_
   k.step_size = st->c[5]; k.rsb2 = st->c[6]; k.eps = st->c[7]; k.gm = st->c[8];
 
   uint32_t cur = 0xffffffffu;
-  cgu32x2_ptr gp = nullptr;
+  g_ptr gp = nullptr;
   gf32x4_ptr wp = nullptr, mp = nullptr, vp = nullptr;
   gu32x2_ptr pp = nullptr;
   for (uint32_t T = blockIdx.x; T < total_tiles; T += gridDim.x) {
@@ -174,7 +200,7 @@ k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_
     if (ci != cur) {
       cur = ci;
       const uint32_t col = first_col + ci;
-      gp = (cgu32x2_ptr)(table[size_t(ROW_GRAD) * table_cols + col]);
+      gp = (g_ptr)(table[size_t(ROW_GRAD) * table_cols + col]);
       wp = (gf32x4_ptr)(table[size_t(ROW_MASTER) * table_cols + col]);
       mp = (gf32x4_ptr)(table[size_t(ROW_M) * table_cols + col]);
       vp = (gf32x4_ptr)(table[size_t(ROW_V) * table_cols + col]);
@@ -212,15 +238,16 @@ k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_
             if (e < nd_ranges[2 * size_t(r) + 1]) d = 1.0f;
           dk[j] = d;
         }
-        u32x2 g = gp[u]; f32x4 w = wp[u], m = mp[u], v = vp[u]; u32x2 p;
-        update_unit<DT>(k, dk, g, w, m, v, p);
+        gvec g = gp[u]; f32x4 w = wp[u], m = mp[u], v = vp[u]; u32x2 p;
+        update_unit<DT, GF32>(k, dk, g, w, m, v, p);
         wp[u] = w; mp[u] = m; vp[u] = v; pp[u] = p;
+        if (zero_grads) gp[u] = gzero;
       }
       continue;
     }
     const float dk[4] = {dtile, dtile, dtile, dtile};
     if ((uint64_t(tile) + 1) * TILE_UNITS <= units) {
-      u32x2 g[UNROLL]; f32x4 w[UNROLL], m[UNROLL], v[UNROLL];
+      gvec g[UNROLL]; f32x4 w[UNROLL], m[UNROLL], v[UNROLL];
 #pragma unroll
       for (int r = 0; r < UNROLL; ++r) {
         const uint64_t u = u0 + uint64_t(r) * AW_THREADS;
@@ -233,34 +260,42 @@ k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_
       for (int r = 0; r < UNROLL; ++r) {
         const uint64_t u = u0 + uint64_t(r) * AW_THREADS;
         u32x2 p;
-        update_unit<DT>(k, dk, g[r], w[r], m[r], v[r], p);
+        update_unit<DT, GF32>(k, dk, g[r], w[r], m[r], v[r], p);
         st_stream<NT>(w[r], wp + u);
         st_stream<NT>(m[r], mp + u);
         st_stream<NT>(v[r], vp + u);
         st_stream<NT>(p, pp + u);
+        if (zero_grads) st_stream<NT>(gzero, gp + u);
       }
     } else {
       // ragged last tile of a chunk
       for (uint64_t u = u0; u < units; u += AW_THREADS) {
-        u32x2 g = gp[u]; f32x4 w = wp[u], m = mp[u], v = vp[u]; u32x2 p;
-        update_unit<DT>(k, dk, g, w, m, v, p);
+        gvec g = gp[u]; f32x4 w = wp[u], m = mp[u], v = vp[u]; u32x2 p;
+        update_unit<DT, GF32>(k, dk, g, w, m, v, p);
         wp[u] = w; mp[u] = m; vp[u] = v; pp[u] = p;
+        if (zero_grads) gp[u] = gzero;
       }
     }
   }
 }
 
 typedef void (*adamw_kernel_t)(const uint64_t*, uint32_t, uint32_t, uint32_t, uint64_t, uint32_t,
-                               const PtDevState*, int, const uint32_t*, const uint64_t*, uint32_t);
+                               const PtDevState*, int, const uint32_t*, const uint64_t*, uint32_t, int);
 
-template <int DT, bool MASKED>
-adamw_kernel_t pick_kernel(uint32_t unroll, bool nt) {
+template <int DT, bool MASKED, bool GF32>
+adamw_kernel_t pick_unroll(uint32_t unroll, bool nt) {
   switch (unroll) {
-    case 1: return nt ? k_adamw<DT, 1, true, MASKED> : k_adamw<DT, 1, false, MASKED>;
-    case 2: return nt ? k_adamw<DT, 2, true, MASKED> : k_adamw<DT, 2, false, MASKED>;
-    case 8: return nt ? k_adamw<DT, 8, true, MASKED> : k_adamw<DT, 8, false, MASKED>;
-    default: return nt ? k_adamw<DT, 4, true, MASKED> : k_adamw<DT, 4, false, MASKED>;
+    case 1: return nt ? k_adamw<DT, 1, true, MASKED, GF32> : k_adamw<DT, 1, false, MASKED, GF32>;
+    case 2: return nt ? k_adamw<DT, 2, true, MASKED, GF32> : k_adamw<DT, 2, false, MASKED, GF32>;
+    case 8: return nt ? k_adamw<DT, 8, true, MASKED, GF32> : k_adamw<DT, 8, false, MASKED, GF32>;
+    default: return nt ? k_adamw<DT, 4, true, MASKED, GF32> : k_adamw<DT, 4, false, MASKED, GF32>;
   }
+}
+
+template <int DT>
+adamw_kernel_t pick_kernel(uint32_t unroll, bool nt, bool masked, bool gf32) {
+  if (masked) return gf32 ? pick_unroll<DT, true, true>(unroll, nt) : pick_unroll<DT, true, false>(unroll, nt);
+  return gf32 ? pick_unroll<DT, false, true>(unroll, nt) : pick_unroll<DT, false, false>(unroll, nt);
 }
 
 }  // namespace
@@ -280,7 +315,7 @@ int pt_prepare_consts(pt_ctx* ctx, const pt_hparams* hp, hipStream_t stream) {
 }
 
 int pt_launch_adamw(pt_ctx* ctx, uint32_t first_col, uint32_t n_cols, hipStream_t stream, bool recast_on_skip,
-                    uint32_t mask_chunk0) {
+                    uint32_t mask_chunk0, bool zero_grads) {
   if (n_cols == 0) return PT_OK;
   const uint32_t unroll = ctx->opt_adamw_unroll;
   const uint64_t units = ctx->S / 4;
@@ -295,12 +330,11 @@ int pt_launch_adamw(pt_ctx* ctx, uint32_t first_col, uint32_t n_cols, hipStream_
   if (ctx->opt_adamw_grid == 0 && want < PT_ADAMW_MIN_GRID) want = PT_ADAMW_MIN_GRID;
   dim3 grid(want < total ? want : total);
   const bool nt = ctx->opt_adamw_nt != 0, masked = ctx->d_nd_begin != nullptr;
-  adamw_kernel_t kern = ctx->dtype == PT_BF16
-      ? (masked ? pick_kernel<PT_BF16, true>(unroll, nt) : pick_kernel<PT_BF16, false>(unroll, nt))
-      : (masked ? pick_kernel<PT_FP16, true>(unroll, nt) : pick_kernel<PT_FP16, false>(unroll, nt));
+  adamw_kernel_t kern = ctx->dtype == PT_BF16 ? pick_kernel<PT_BF16>(unroll, nt, masked, ctx->grad_f32)
+                                              : pick_kernel<PT_FP16>(unroll, nt, masked, ctx->grad_f32);
   hipLaunchKernelGGL(kern, grid, dim3(AW_THREADS), 0, stream, ctx->d_table, ctx->table_cols, first_col, n_cols,
                      ctx->S, uint32_t(tpc), ctx->d_state, recast_on_skip ? 1 : 0, ctx->d_nd_begin, ctx->d_nd_ranges,
-                     mask_chunk0);
+                     mask_chunk0, zero_grads ? 1 : 0);
   PT_LAUNCH_CHECK(ctx, "k_adamw");
   return PT_OK;
 }
@@ -326,5 +360,5 @@ extern "C" int pt_chunk_adamw_step(pt_ctx* ctx, const pt_hparams* hp, uint32_t f
   if ((rc = pt_table_bind(ctx, ROW_V, first_chunk, n_chunks, (const void* const*)v, false, st, nullptr)) != PT_OK) return rc;
   if ((rc = pt_table_bind(ctx, ROW_P16, first_chunk, n_chunks, (const void* const*)param16, false, st, nullptr)) != PT_OK) return rc;
   if ((rc = pt_prepare_consts(ctx, hp, st)) != PT_OK) return rc;
-  return pt_launch_adamw(ctx, first_chunk, n_chunks, st, false, first_chunk);
+  return pt_launch_adamw(ctx, first_chunk, n_chunks, st, false, first_chunk, ctx->opt_zero_grads != 0);
 }

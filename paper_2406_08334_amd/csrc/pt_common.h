@@ -90,6 +90,8 @@ struct pt_ctx {
   uint32_t opt_adamw_nt = 1;        // non-temporal hints on the update's loads and stores
   uint32_t opt_pack_tile_elems = PT_PACK_TILE_ELEMS;  // read when a pack plan is created
   bool scaler = false;
+  bool grad_f32 = false;            // gradient chunks hold fp32 (accumulated micro-batches), option "grad_fp32"
+  uint32_t opt_zero_grads = 0;      // pt_chunk_adamw_step zeroes the gradient chunks it has read
 
   PtDevState* d_state = nullptr;
   uint64_t* d_table = nullptr;          // [N_ROWS][table_cols]
@@ -164,8 +166,9 @@ inline const uint64_t* pt_row(const pt_ctx* ctx, int row) {
 int pt_prepare_consts(pt_ctx* ctx, const pt_hparams* hp, hipStream_t stream);
 // recast_on_skip: on a skipped step rewrite param16 = RNE(master) instead of doing nothing.
 // mask_chunk0: chunk index (for the no-decay ranges) of table column first_col.
+// zero_grads: overwrite the gradient chunks with zeros once read (resident chunks only).
 int pt_launch_adamw(pt_ctx* ctx, uint32_t first_col, uint32_t n_cols, hipStream_t stream, bool recast_on_skip,
-                    uint32_t mask_chunk0);
+                    uint32_t mask_chunk0, bool zero_grads);
 
 // ---- implemented in pt_norm.hip ---------------------------------------------------------
 // Sums per-block partials into per-chunk values.  uniform mode (tile_begin == NULL):

@@ -221,6 +221,17 @@ extern "C" int pt_ctx_set_option(pt_ctx* ctx, const char* name, int64_t value) {
     ctx->opt_adamw_nt = value != 0;
     return PT_OK;
   }
+  if (std::strcmp(name, "adamw_zero_grads") == 0) {
+    ctx->opt_zero_grads = value != 0;
+    return PT_OK;
+  }
+  if (std::strcmp(name, "grad_fp32") == 0) {
+    if (ctx->n_slots && (value != 0) != ctx->grad_f32)
+      return pt_fail(ctx, PT_ERR_STATE, "grad_fp32 must be chosen before pt_stream_reserve (the chunk buffers are sized by it)");
+    ctx->grad_f32 = value != 0;
+    ctx->norm_finalized = false;
+    return PT_OK;
+  }
   return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_ctx_set_option: unknown option '%s'", name);
 }
 

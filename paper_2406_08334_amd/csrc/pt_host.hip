@@ -78,6 +78,21 @@ void host_update_bf16(const HostConsts k, const uint16_t* __restrict__ g, float*
   PT_HOST_UPDATE_BODY(bf16_to_f32, f32_to_bf16)
 }
 
+inline float f32_identity(float x) { return x; }
+
+// fp32 gradient chunks (accumulated micro-batches): the gradient is read as it is
+PT_HOST_CLONES
+void host_update_bf16_g32(const HostConsts k, const float* __restrict__ g, float* __restrict__ w,
+                          float* __restrict__ m, float* __restrict__ v, uint16_t* __restrict__ p, uint64_t n) {
+  PT_HOST_UPDATE_BODY(f32_identity, f32_to_bf16)
+}
+
+PT_HOST_CLONES
+void host_update_fp16_g32(const HostConsts k, const float* __restrict__ g, float* __restrict__ w,
+                          float* __restrict__ m, float* __restrict__ v, uint16_t* __restrict__ p, uint64_t n) {
+  PT_HOST_UPDATE_BODY(f32_identity, f32_to_fp16)
+}
+
 PT_HOST_CLONES
 void host_update_fp16(const HostConsts k, const uint16_t* __restrict__ g, float* __restrict__ w,
                       float* __restrict__ m, float* __restrict__ v, uint16_t* __restrict__ p, uint64_t n) {
@@ -126,7 +141,7 @@ extern "C" int pt_chunk_host_adamw_step(pt_ctx* ctx, const pt_hparams* hp, uint3
   const uint64_t total_grains = grains_per_chunk * n_chunks;
   std::atomic<uint64_t> next{0};
   const int dtype = ctx->dtype;
-  const bool masked = !ctx->h_nd_begin.empty();
+  const bool masked = !ctx->h_nd_begin.empty(), gf32 = ctx->grad_f32;
   const uint32_t* nd_begin = ctx->h_nd_begin.data();
   const uint64_t* nd_ranges = ctx->h_nd_ranges.data();
   auto worker = [&]() {
@@ -135,7 +150,8 @@ extern "C" int pt_chunk_host_adamw_step(pt_ctx* ctx, const pt_hparams* hp, uint3
       if (gidx >= total_grains) return;
       const uint64_t c = gidx / grains_per_chunk, lo = (gidx % grains_per_chunk) * HOST_GRAIN;
       const uint64_t n = (lo + HOST_GRAIN <= S) ? HOST_GRAIN : S - lo;
-      const uint16_t* g = static_cast<const uint16_t*>(h_grad[c]) + lo;
+      const uint16_t* g = static_cast<const uint16_t*>(h_grad[c]) + lo;       // 16-bit gradient chunks
+      const float* g32 = static_cast<const float*>(h_grad[c]) + lo;          // fp32 gradient chunks
       uint16_t* p = static_cast<uint16_t*>(h_param16[c]) + lo;
       // runs of one decay factor: between and inside the chunk's no-decay ranges
       uint64_t pos = lo;
@@ -151,8 +167,14 @@ extern "C" int pt_chunk_host_adamw_step(pt_ctx* ctx, const pt_hparams* hp, uint3
           else { kk.decay = 1.0f; stop = std::min<uint64_t>(end, nd_ranges[2 * size_t(r) + 1]); ++r; }
         }
         const uint64_t off = pos - lo, cnt = stop - pos;
-        if (dtype == PT_BF16) host_update_bf16(kk, g + off, h_master[c] + pos, h_m[c] + pos, h_v[c] + pos, p + off, cnt);
-        else host_update_fp16(kk, g + off, h_master[c] + pos, h_m[c] + pos, h_v[c] + pos, p + off, cnt);
+        float* w_ = h_master[c] + pos; float* m_ = h_m[c] + pos; float* v_ = h_v[c] + pos;
+        if (gf32) {
+          if (dtype == PT_BF16) host_update_bf16_g32(kk, g32 + off, w_, m_, v_, p + off, cnt);
+          else host_update_fp16_g32(kk, g32 + off, w_, m_, v_, p + off, cnt);
+        } else {
+          if (dtype == PT_BF16) host_update_bf16(kk, g + off, w_, m_, v_, p + off, cnt);
+          else host_update_fp16(kk, g + off, w_, m_, v_, p + off, cnt);
+        }
         pos = stop;
       }
     }

@@ -113,6 +113,59 @@ k_sqnorm(const uint64_t* __restrict__ grad_row, uint32_t first, uint64_t S,
   }
 }
 
+// The same reduction over fp32 gradient chunks (accumulated micro-batches): 4 bytes read per
+// element, every value widened to fp64 before it is scaled and squared.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void accum_vec_f32(const f32x4& q, double inv_scale, double& a0, double& a1,
+                                              uint32_t& flag) {
+#pragma unroll
+  for (int k = 0; k < 4; k += 2) {
+    double x0 = (double)q[k] * inv_scale;
+    double x1 = (double)q[k + 1] * inv_scale;
+    a0 = fma(x0, x0, a0);
+    a1 = fma(x1, x1, a1);
+    flag |= uint32_t((__float_as_uint(q[k]) & 0x7f800000u) == 0x7f800000u) |
+            uint32_t((__float_as_uint(q[k + 1]) & 0x7f800000u) == 0x7f800000u);
+  }
+}
+
+__global__ void __launch_bounds__(NB_THREADS)
+k_sqnorm_f32(const uint64_t* __restrict__ grad_row, uint32_t first, uint64_t S,
+             const PtDevState* __restrict__ st, double* __restrict__ part, uint32_t* __restrict__ flagout) {
+  const uint32_t b = blockIdx.x, i = blockIdx.y;
+  const PT_GLOBAL f32x4* base = (const PT_GLOBAL f32x4*)(grad_row[first + i]);
+  const uint64_t vec_total = S / 4;
+  const uint64_t v0 = uint64_t(b) * (PT_NORM_BLOCK_ELEMS / 4);
+  uint64_t v1 = v0 + PT_NORM_BLOCK_ELEMS / 4;
+  if (v1 > vec_total) v1 = vec_total;
+  const double inv_scale = 1.0 / st->loss_scale;
+  double a0 = 0.0, a1 = 0.0;
+  uint32_t flag = 0;
+  uint64_t v = v0 + threadIdx.x;
+  for (; v + 3 * NB_THREADS < v1; v += 4 * NB_THREADS) {
+    f32x4 q0 = __builtin_nontemporal_load(base + v);
+    f32x4 q1 = __builtin_nontemporal_load(base + v + NB_THREADS);
+    f32x4 q2 = __builtin_nontemporal_load(base + v + 2 * NB_THREADS);
+    f32x4 q3 = __builtin_nontemporal_load(base + v + 3 * NB_THREADS);
+    accum_vec_f32(q0, inv_scale, a0, a1, flag);
+    accum_vec_f32(q1, inv_scale, a0, a1, flag);
+    accum_vec_f32(q2, inv_scale, a0, a1, flag);
+    accum_vec_f32(q3, inv_scale, a0, a1, flag);
+  }
+  for (; v < v1; v += NB_THREADS) {
+    f32x4 q = __builtin_nontemporal_load(base + v);
+    accum_vec_f32(q, inv_scale, a0, a1, flag);
+  }
+  double acc = a0 + a1;
+  block_sum(acc, flag);
+  if (threadIdx.x == 0) {
+    size_t slot = size_t(i) * gridDim.x + b;
+    part[slot] = acc;
+    flagout[slot] = flag;
+  }
+}
+
 // One block per chunk: sums that chunk's partials (lane-strided serial sums, then
 // the fixed block tree).  tile_begin == NULL: chunk first+i owns
 // [i*per_chunk, (i+1)*per_chunk); otherwise [tile_begin[c], tile_begin[c+1]) and a
@@ -169,7 +222,10 @@ extern "C" int pt_chunk_grad_sqnorm(pt_ctx* ctx, const void* const* grad_chunks,
     int rc = pt_table_bind(ctx, ROW_PACK, first_chunk, n_chunks, grad_chunks + first_chunk, false, st, nullptr);
     if (rc != PT_OK) return rc;
     dim3 grid(ctx->norm_blocks, n_chunks);
-    if (ctx->dtype == PT_BF16)
+    if (ctx->grad_f32)
+      hipLaunchKernelGGL(k_sqnorm_f32, grid, dim3(NB_THREADS), 0, st, pt_row(ctx, ROW_PACK), first_chunk,
+                         ctx->S, ctx->d_state, ctx->d_norm_part, ctx->d_norm_flag);
+    else if (ctx->dtype == PT_BF16)
       hipLaunchKernelGGL(k_sqnorm<PT_BF16>, grid, dim3(NB_THREADS), 0, st, pt_row(ctx, ROW_PACK), first_chunk,
                          ctx->S, ctx->d_state, ctx->d_norm_part, ctx->d_norm_flag);
     else

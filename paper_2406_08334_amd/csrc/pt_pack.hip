@@ -193,7 +193,10 @@ extern "C" int pt_pack_plan_create(pt_ctx* ctx, const pt_segment* segs, uint32_t
       return pt_fail(ctx, PT_ERR_INVALID_ARG, "segments %u and %u overlap in chunk %u", order[k - 1], order[k], p.chunk);
   }
   // cut into tiles at multiples of the tile size in chunk space
-  const uint64_t tile_elems = ctx->opt_pack_tile_elems;
+  // With fp32 gradient chunks the plan feeds the accumulate kernel, which moves 2.5 times the
+  // bytes per element: half the tile gives it the same short-lived workgroups (measured best).
+  const uint64_t tile_elems = ctx->grad_f32 ? std::max<uint64_t>(1024, ctx->opt_pack_tile_elems / 2)
+                                            : ctx->opt_pack_tile_elems;
   std::vector<PtTile> tiles;
   std::vector<uint32_t> begin(size_t(ctx->C) + 1, 0);
   uint64_t total = 0;
@@ -277,6 +280,8 @@ static int run_pack(pt_ctx* ctx, const pt_pack_plan* plan, const void* const* ch
 
 extern "C" int pt_chunk_pack_grads(pt_ctx* ctx, const pt_pack_plan* plan, void* const* grad_chunks, void* stream) {
   if (!ctx) return PT_ERR_INVALID_ARG;
+  if (ctx->grad_f32)
+    return pt_fail(ctx, PT_ERR_STATE, "pt_chunk_pack_grads: this context holds fp32 gradient chunks; use pt_chunk_accum_grads");
   return run_pack<0>(ctx, plan, (const void* const*)grad_chunks, ROW_PACK, (hipStream_t)stream, "pt_chunk_pack_grads");
 }
 

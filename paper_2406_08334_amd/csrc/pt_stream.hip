@@ -7,13 +7,15 @@
 // against 28 bytes of HBM traffic in the kernel.
 #include "pt_common.h"
 
-// One device chunk buffer ("slot"), 16 bytes per element:
-//   [ master S*4 | m S*4 | v S*4 | grad S*2 | param16 S*2 ]
+// One device chunk buffer ("slot"), 16 bytes per element (18 with fp32 gradient chunks):
+//   [ master S*4 | m S*4 | v S*4 | grad S*2 or S*4 | param16 S*2 ]
+static inline size_t grad_bytes(const pt_ctx* c) { return c->grad_f32 ? 4 : 2; }
+static inline size_t slot_bytes(const pt_ctx* c) { return (14 + grad_bytes(c)) * size_t(c->S); }
 static inline char* slot_master(const pt_ctx* c, uint32_t s) { return (char*)c->slot_mem[s]; }
 static inline char* slot_m(const pt_ctx* c, uint32_t s) { return (char*)c->slot_mem[s] + 4 * c->S; }
 static inline char* slot_v(const pt_ctx* c, uint32_t s) { return (char*)c->slot_mem[s] + 8 * c->S; }
 static inline char* slot_grad(const pt_ctx* c, uint32_t s) { return (char*)c->slot_mem[s] + 12 * c->S; }
-static inline char* slot_p16(const pt_ctx* c, uint32_t s) { return (char*)c->slot_mem[s] + 14 * c->S; }
+static inline char* slot_p16(const pt_ctx* c, uint32_t s) { return (char*)c->slot_mem[s] + (12 + grad_bytes(c)) * c->S; }
 
 extern "C" int pt_stream_reserve(pt_ctx* ctx, uint32_t n_slots) {
   if (!ctx) return PT_ERR_INVALID_ARG;
@@ -29,11 +31,11 @@ extern "C" int pt_stream_reserve(pt_ctx* ctx, uint32_t n_slots) {
     PT_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_up[s], hipEventDisableTiming));
     PT_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_k[s], hipEventDisableTiming));
     PT_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_down[s], hipEventDisableTiming));
-    hipError_t e = hipMalloc(&ctx->slot_mem[s], size_t(16) * ctx->S);
+    hipError_t e = hipMalloc(&ctx->slot_mem[s], slot_bytes(ctx));
     if (e != hipSuccess)
       return pt_fail(ctx, e == hipErrorOutOfMemory ? PT_ERR_NOMEM : PT_ERR_HIP,
                      "pt_stream_reserve: hipMalloc of chunk buffer %u (%llu bytes) failed: %s", s,
-                     (unsigned long long)(16 * ctx->S), hipGetErrorString(e));
+                     (unsigned long long)slot_bytes(ctx), hipGetErrorString(e));
     // the buffer's five arrays become column C+s of the pointer table
     const void* p;
     int rc;
@@ -84,14 +86,14 @@ extern "C" int pt_chunk_stream_step(pt_ctx* ctx, const pt_hparams* hp, uint32_t 
     const uint32_t s = i % ctx->n_slots;
     // upload: the slot must have been offloaded by its previous tenant
     if (ctx->slot_used[s]) PT_HIP(ctx, hipStreamWaitEvent(ctx->s_up, ctx->ev_down[s], 0));
-    PT_HIP(ctx, hipMemcpyAsync(slot_grad(ctx, s), h_grad[i], 2 * S, hipMemcpyHostToDevice, ctx->s_up));
+    PT_HIP(ctx, hipMemcpyAsync(slot_grad(ctx, s), h_grad[i], grad_bytes(ctx) * S, hipMemcpyHostToDevice, ctx->s_up));
     PT_HIP(ctx, hipMemcpyAsync(slot_master(ctx, s), h_master[i], 4 * S, hipMemcpyHostToDevice, ctx->s_up));
     PT_HIP(ctx, hipMemcpyAsync(slot_m(ctx, s), h_m[i], 4 * S, hipMemcpyHostToDevice, ctx->s_up));
     PT_HIP(ctx, hipMemcpyAsync(slot_v(ctx, s), h_v[i], 4 * S, hipMemcpyHostToDevice, ctx->s_up));
     PT_HIP(ctx, hipEventRecord(ctx->ev_up[s], ctx->s_up));
     // update on the slot
     PT_HIP(ctx, hipStreamWaitEvent(ctx->s_comp, ctx->ev_up[s], 0));
-    if ((rc = pt_launch_adamw(ctx, ctx->C + s, 1, ctx->s_comp, true, first_chunk + i)) != PT_OK) return rc;
+    if ((rc = pt_launch_adamw(ctx, ctx->C + s, 1, ctx->s_comp, true, first_chunk + i, false)) != PT_OK) return rc;
     PT_HIP(ctx, hipEventRecord(ctx->ev_k[s], ctx->s_comp));
     // offload
     PT_HIP(ctx, hipStreamWaitEvent(ctx->s_down, ctx->ev_k[s], 0));

@@ -28,7 +28,7 @@ class ChunkedState:
     that arena.view(-1) IS the flat concatenation (plus padding) the oracle works on."""
 
     def __init__(self, sizes, S, dtype=torch.bfloat16, scaler=None, param_std=0.02, seed=0,
-                 resident=None, init_params=True):
+                 resident=None, init_params=True, grad_fp32=False):
         self.sizes = [int(s) for s in sizes]
         self.S = int(S)
         self.N = sum(self.sizes)
@@ -41,6 +41,10 @@ class ChunkedState:
         dev = "cuda"
         C, S = self.C, self.S
         self.ctx = B.pt_ctx_create(self.pt_dtype, S, C, scaler)
+        self.grad_fp32 = grad_fp32
+        if grad_fp32:                      # micro-batches are accumulated into fp32 gradient chunks
+            B.pt_ctx_set_option(self.ctx, "grad_fp32", 1)
+            self.g32 = torch.zeros(C, S, dtype=torch.float32, device=dev)
         # gradient tensors: one flat buffer, tensor t at the running offset (so odd sizes give
         # sources that are only 2-byte aligned)
         self.grad_src = torch.zeros(max(self.N, 1), dtype=dtype, device=dev)
@@ -64,21 +68,29 @@ class ChunkedState:
         hi = self.C if hi is None else hi
         return [arena[c] for c in range(lo, hi)]
 
-    def set_grads(self, step, std=1e-3, scale=1.0, outlier_every=0):
+    def set_grads(self, step, std=1e-3, scale=1.0, outlier_every=0, micro=0):
         if self.N:
-            synth.normal_16(synth.SEED_GRADS + self.seed, step, 0, 0, self.N, std, self.dtype, "cuda",
+            synth.normal_16(synth.SEED_GRADS + self.seed, step, micro, 0, self.N, std, self.dtype, "cuda",
                             scale=scale, outlier_every=outlier_every, out=self.grad_src[:self.N])
+
+    @property
+    def grads(self):
+        """the gradient chunks the norm and the update read"""
+        return self.g32 if self.grad_fp32 else self.g16
+
+    def accum(self, overwrite, take_norm):
+        B.pt_chunk_accum_grads(self.ctx, self.plan, self.rows(self.g32), overwrite, take_norm)
 
     # ---- the calls
     def pack(self):
         B.pt_chunk_pack_grads(self.ctx, self.plan, self.rows(self.g16))
 
     def norm(self, recompute=False, finalize=True):
-        B.pt_chunk_grad_sqnorm(self.ctx, self.rows(self.g16) if recompute else None, 0, self.C, finalize)
+        B.pt_chunk_grad_sqnorm(self.ctx, self.rows(self.grads) if recompute else None, 0, self.C, finalize)
 
     def adamw(self, hp, lo=0, hi=None):
         hi = self.C if hi is None else hi
-        B.pt_chunk_adamw_step(self.ctx, hp, lo, hi - lo, self.rows(self.g16, lo, hi), self.rows(self.w, lo, hi),
+        B.pt_chunk_adamw_step(self.ctx, hp, lo, hi - lo, self.rows(self.grads, lo, hi), self.rows(self.w, lo, hi),
                               self.rows(self.m, lo, hi), self.rows(self.v, lo, hi), self.rows(self.p16, lo, hi))
 
     def end(self):
@@ -107,9 +119,12 @@ class ChunkedState:
     # ---- host copies for the oracle
     def host_state(self):
         torch.cuda.synchronize()
-        return dict(g16=to_u16(self.g16).reshape(-1).copy(), p16=to_u16(self.p16).reshape(-1).copy(),
-                    w=self.w.cpu().numpy().reshape(-1).copy(), m=self.m.cpu().numpy().reshape(-1).copy(),
-                    v=self.v.cpu().numpy().reshape(-1).copy())
+        out = dict(g16=to_u16(self.g16).reshape(-1).copy(), p16=to_u16(self.p16).reshape(-1).copy(),
+                   w=self.w.cpu().numpy().reshape(-1).copy(), m=self.m.cpu().numpy().reshape(-1).copy(),
+                   v=self.v.cpu().numpy().reshape(-1).copy())
+        if self.grad_fp32:
+            out["g32"] = self.g32.cpu().numpy().reshape(-1).copy()
+        return out
 
     def close(self):
         torch.cuda.synchronize()
