@@ -157,7 +157,10 @@ def run_streamed(args) -> int:
     def one_step(streamed=True, resident=True, on_host=False):
         B.pt_chunk_pack_grads(ctx, plan, pack_rows, stream)
         B.pt_chunk_grad_sqnorm(ctx, None, 0, C, True, stream)
-        if streamed and not on_host:
+        if streamed and not on_host and args.zero_copy:
+            # the update kernel reads and writes the pinned host chunks itself, over the link
+            B.pt_chunk_adamw_step(ctx, hp, n_persist, n_host, h_g, h_w, h_m, h_v, h_p, stream)
+        elif streamed and not on_host:
             B.pt_chunk_stream_step(ctx, hp, n_persist, n_host, h_g, h_w, h_m, h_v, h_p, stream)
         if resident:
             B.pt_chunk_adamw_step(ctx, hp, 0, n_persist, r_g, r_w, r_m, r_v, r_p, stream)
@@ -290,7 +293,6 @@ def run_streamed(args) -> int:
         "link_utilisation_vs_bare_bidirectional": round(per_dir / ref, 4),
         "ms_resident_only": round(1e3 * t_res, 2), "ms_streamed_only": round(1e3 * t_str, 2),
         "overlap_ratio_step_over_max": round(t_step / max(t_res, t_str), 4),
-        "fill_GBps": round(fill_bytes / (mean(pack_ms) * 1e-3) / 1e9, 1),
         "step_report": {"norm": rep.norm, "found_inf": rep.found_inf, "step": rep.step},
     }
     if host_update:
@@ -365,6 +367,8 @@ def main() -> int:
     ap.add_argument("--stream", action="store_true",
                     help="the streamed configuration instead: LLaMA-13B shape, first half of the chunks resident, "
                          "the rest in pinned host memory through pt_chunk_stream_step")
+    ap.add_argument("--zero-copy", action="store_true",
+                    help="--stream: no chunk buffers; the update kernel accesses the pinned host chunks directly")
     ap.add_argument("--host-chunks", type=int, default=0, help="--stream: host-resident chunks (default: all of the second half)")
     ap.add_argument("--slots", type=int, default=3, help="--stream: device chunk buffers")
     ap.add_argument("--host-update", action="store_true",
