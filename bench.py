@@ -322,6 +322,8 @@ def run_in_processes(args) -> int:
         if args.no_decay_1d: cmd.append("--no-decay-1d")
         if args.grad_accum: cmd += ["--grad-accum", str(args.grad_accum)]
         if args.zero_grads: cmd.append("--zero-grads")
+        if args.fp16: cmd.append("--fp16")
+        if args.graph: cmd.append("--graph")
         if args.pack_tile: cmd += ["--pack-tile", str(args.pack_tile)]
         if args.no_cpu_baseline or i != args.processes - 1: cmd.append("--no-cpu-baseline")
         res = subprocess.run(cmd, stdout=subprocess.PIPE, text=True)
@@ -358,6 +360,10 @@ def main() -> int:
     ap.add_argument("--grad-accum", type=int, default=0, metavar="K",
                     help="variant: K micro-batches accumulated into fp32 gradient chunks per step (0 = the 16-bit pack path)")
     ap.add_argument("--pack-tile", type=int, default=0, help="elements one workgroup of pack / accumulate moves (0 = default)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the whole step replayed from a HIP graph (one gradient set); reported beside the eager figure")
+    ap.add_argument("--fp16", action="store_true",
+                    help="fp16 parameters and gradients with dynamic loss scaling (scale 2^16; gradients drawn scaled)")
     ap.add_argument("--zero-grads", action="store_true", help="variant: the update zeroes the gradient chunks it has read")
     ap.add_argument("--processes", type=int, default=2,
                     help="measure in this many fresh processes one after the other and report the best "
@@ -383,7 +389,7 @@ def main() -> int:
         return 2
     if args.stream:
         return run_streamed(args)
-    if args.layout == "grouped" or args.no_decay_1d or args.grad_accum or args.zero_grads:
+    if args.layout == "grouped" or args.no_decay_1d or args.grad_accum or args.zero_grads or args.fp16:
         args.no_cpu_baseline = True      # the oracle leg samples the dense layout's first chunks, all decayed
     if not args.child and args.processes > 1:
         return run_in_processes(args)
@@ -423,7 +429,11 @@ def main() -> int:
         f"state {16 * N_pad / 1e9:.2f} GB + {n_sets} gradient sets of {2 * N / 1e9:.2f} GB")
 
     t0 = time.time()
-    ctx = B.pt_ctx_create(B.PT_BF16, S, C, None)
+    dt16 = torch.float16 if args.fp16 else torch.bfloat16
+    sigma = 65536.0 if args.fp16 else 1.0
+    ctx = B.pt_ctx_create(B.PT_FP16 if args.fp16 else B.PT_BF16, S, C,
+                          B.pt_scaler_cfg(sigma, 2.0, 0.5, 2000, 0) if args.fp16 else None)
+    outlier_every = 1000 if args.workload == "gpt2_xl" else 0      # 0.1 % of the gradients x100: clipping triggers
     if args.no_decay_1d:
         one_d = {i for i, (name, _) in enumerate(table) if name.endswith(".bias") or "norm" in name or ".ln_" in name}
         nd = [B.pt_segment(0, 0, s.len, s.chunk_off, s.chunk, s.tensor) for s in segs if s.tensor in one_d]
@@ -437,13 +447,13 @@ def main() -> int:
     if args.zero_grads:
         B.pt_ctx_set_option(ctx, "adamw_zero_grads", 1)
         layout_note += "; gradients zeroed by the update"
-    g16 = torch.zeros(C, S, dtype=torch.float32 if args.grad_accum else torch.bfloat16, device=dev)
-    p16 = torch.zeros(C, S, dtype=torch.bfloat16, device=dev)
+    g16 = torch.zeros(C, S, dtype=torch.float32 if args.grad_accum else dt16, device=dev)
+    p16 = torch.zeros(C, S, dtype=dt16, device=dev)
     offs = np.cumsum([0] + sizes[:-1]).tolist()
     if args.layout == "grouped":
         # parameters are generated as the model's tensors and brought into chunk space by the same copy
-        flat = torch.empty(N, dtype=torch.bfloat16, device=dev)
-        synth.normal_16(synth.SEED_PARAMS, 0, 0, 0, N, 0.02, torch.bfloat16, dev, out=flat)
+        flat = torch.empty(N, dtype=dt16, device=dev)
+        synth.normal_16(synth.SEED_PARAMS, 0, 0, 0, N, 0.02, dt16, dev, out=flat)
         for s in segs:
             s.src = flat.data_ptr() + 2 * offs[s.tensor]
         plan0 = B.pt_pack_plan_create(ctx, segs)
@@ -452,7 +462,7 @@ def main() -> int:
         B.pt_pack_plan_destroy(plan0)
         del flat
     else:
-        synth.normal_16(synth.SEED_PARAMS, 0, 0, 0, N, 0.02, torch.bfloat16, dev, out=p16.view(-1)[:N])
+        synth.normal_16(synth.SEED_PARAMS, 0, 0, 0, N, 0.02, dt16, dev, out=p16.view(-1)[:N])
     w = torch.empty(C, S, dtype=torch.float32, device=dev)
     for c in range(C):
         w[c].copy_(p16[c])
@@ -460,8 +470,8 @@ def main() -> int:
     v = torch.zeros(C, S, dtype=torch.float32, device=dev)
     grad_sets, plans = [], []
     for k in range(n_sets):
-        gs = torch.empty(N, dtype=torch.bfloat16, device=dev)
-        synth.normal_16(synth.SEED_GRADS, k + 1, 0, 0, N, 1e-3, torch.bfloat16, dev, out=gs)
+        gs = torch.empty(N, dtype=dt16, device=dev)
+        synth.normal_16(synth.SEED_GRADS, k + 1, 0, 0, N, 1e-3, dt16, dev, scale=sigma, outlier_every=outlier_every, out=gs)
         for s in segs:
             s.src = gs.data_ptr() + 2 * offs[s.tensor]
         grad_sets.append(gs)
@@ -537,7 +547,8 @@ def main() -> int:
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {N} elements in {C} chunks of {S}, {layout_note}, all GPU-resident, "
-                               "bf16 params/grads N(0,0.02)/N(0,1e-3), fp32 master/m/v, AdamW lr 1e-4 betas (0.9,0.95) "
+                               f"{'fp16, loss scale 2^16' if args.fp16 else 'bf16'} params/grads N(0,0.02)/N(0,1e-3)"
+                               f"{' with 0.1 % of the gradients x100' if outlier_every else ''}, fp32 master/m/v, AdamW lr 1e-4 betas (0.9,0.95) "
                                "eps 1e-8 wd 0.1 clip 1.0",
                    "chunk_elems": S, "n_chunks": C, "elements": N, "padded_elements": N_pad,
                    "step_bytes": step_bytes, "grad_sets": n_sets},
@@ -546,11 +557,43 @@ def main() -> int:
                        "adamw(+prepare)": round(mean(adamw_ms), 4)},
         "fill_GBps": round(fill_bytes / (mean(pack_ms) * 1e-3) / 1e9, 1),
         "step_report": {"norm": rep.norm, "clip_coef": rep.clip_coef, "found_inf": rep.found_inf, "step": rep.step},
-        "roofline": {"kernel": "k_adamw<bf16, unroll 4, non-temporal%s%s%s>" % (", no-decay runs" if args.no_decay_1d else "", ", fp32 gradients" if A else "", ", zeroing gradients" if args.zero_grads else ""), "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+        "roofline": {"kernel": "k_adamw<%s, unroll 4, non-temporal%s%s%s>" % ("fp16" if args.fp16 else "bf16", ", no-decay runs" if args.no_decay_1d else "", ", fp32 gradients" if A else "", ", zeroing gradients" if args.zero_grads else ""), "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": MEASURED_TRAFFIC.get(args.workload) if args.layout == "dense" and not A and not args.zero_grads else None,
                      "bytes_per_launch": adamw_bytes, "avg_launch_ms": round(mean(adamw_ms), 4)},
     }
+
+    if args.graph:
+        # the same step captured once and replayed: what is left when launch overhead goes (small states)
+        side = torch.cuda.Stream()
+
+        def step_on(st_):
+            if A:
+                for j in range(A):
+                    B.pt_chunk_accum_grads(ctx, plans[j % n_sets], r_g, j == 0, j == A - 1, st_)
+            else:
+                B.pt_chunk_pack_grads(ctx, plans[0], r_g, st_)
+            B.pt_chunk_grad_sqnorm(ctx, None, 0, C, True, st_)
+            B.pt_chunk_adamw_step(ctx, hp, 0, C, r_g, r_w, r_m, r_v, r_p, st_)
+            B.pt_step_end(ctx, st_)
+
+        with torch.cuda.stream(side):
+            step_on(side)                      # pointer tables are bound outside the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step_on(torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t_g = time.perf_counter()
+        for _ in range(K):
+            graph.replay()
+        torch.cuda.synchronize()
+        t_g = (time.perf_counter() - t_g) / K
+        out["hip_graph"] = {"ms_per_step": round(1e3 * t_g, 4), "GBps": round(step_bytes / t_g / 1e9, 1),
+                            "speedup_over_eager": round(ms_step * 1e-3 / t_g, 3)}
 
     if args.sweep:
         # launch-shape sweep of the update kernel, same process and allocations (stderr only)
