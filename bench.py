@@ -67,14 +67,14 @@ def run_streamed(args) -> int:
     ctx = B.pt_ctx_create(B.PT_BF16, S, C, None)
     B.pt_stream_reserve(ctx, args.slots)
     n_res = n_persist * S
-    g16 = torch.zeros(n_persist, S, dtype=torch.bfloat16, device=dev)
-    p16 = torch.zeros(n_persist, S, dtype=torch.bfloat16, device=dev)
+    from paper_2406_08334_amd.arena import spread_arenas
+    g16, p16, w, m, v = spread_arenas(
+        [((n_persist, S), torch.bfloat16), ((n_persist, S), torch.bfloat16), ((n_persist, S), torch.float32),
+         ((n_persist, S), torch.float32), ((n_persist, S), torch.float32)], device=dev,
+        gap_bytes=0 if args.placement == "plain" else None, keep_free_bytes=2 * n_res + 16 * S)
     synth.normal_16(synth.SEED_PARAMS, 0, 0, 0, n_res, 0.02, torch.bfloat16, dev, out=p16.view(-1))
-    w = torch.empty(n_persist, S, dtype=torch.float32, device=dev)
     for c in range(n_persist):
         w[c].copy_(p16[c])
-    m = torch.zeros(n_persist, S, dtype=torch.float32, device=dev)
-    v = torch.zeros(n_persist, S, dtype=torch.float32, device=dev)
     grad_src = torch.empty(n_res, dtype=torch.bfloat16, device=dev)
     synth.normal_16(synth.SEED_GRADS, 1, 0, 0, n_res, 1e-3, torch.bfloat16, dev, out=grad_src)
     offs = np.cumsum([0] + sizes[:-1]).tolist()
@@ -306,11 +306,11 @@ def run_streamed(args) -> int:
 
 
 def run_in_processes(args) -> int:
-    """The same measurement in several fresh processes, one after the other.  AdamW time on this
-    machine depends on where the driver places the state (about 10 % between a process started on
-    an idle GPU and one started right after another process released the memory), and stays
-    what it is for the life of a process.  The parent never touches the GPU; it prints the
-    best child's line and lists every child's figures under "process_runs"."""
+    """The same measurement in several fresh processes, one after the other (--processes N > 1).  With
+    arenas allocated back to back (--placement plain) the update's speed depends on where the driver
+    places them physically: about 10 % between a process started on an idle GPU and one started right
+    after another process released the memory, for the life of the process.  The parent never touches
+    the GPU; it prints the best child's line and lists every child's figures under "process_runs"."""
     import subprocess
     lines = []
     for i in range(args.processes):
@@ -323,7 +323,9 @@ def run_in_processes(args) -> int:
         if args.grad_accum: cmd += ["--grad-accum", str(args.grad_accum)]
         if args.zero_grads: cmd.append("--zero-grads")
         if args.fp16: cmd.append("--fp16")
+        cmd += ["--placement", args.placement]
         if args.graph: cmd.append("--graph")
+        if args.chunk_map: cmd.append("--chunk-map")
         if args.pack_tile: cmd += ["--pack-tile", str(args.pack_tile)]
         if args.no_cpu_baseline or i != args.processes - 1: cmd.append("--no-cpu-baseline")
         res = subprocess.run(cmd, stdout=subprocess.PIPE, text=True)
@@ -346,8 +348,8 @@ def run_in_processes(args) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama_7b", help="llama_7b | gpt2_xl | gpt2_block_768")
     ap.add_argument("--grad-sets", type=int, default=3, help="distinct pre-generated gradient sets, rotated")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -362,12 +364,19 @@ def main() -> int:
     ap.add_argument("--pack-tile", type=int, default=0, help="elements one workgroup of pack / accumulate moves (0 = default)")
     ap.add_argument("--graph", action="store_true",
                     help="also time the whole step replayed from a HIP graph (one gradient set); reported beside the eager figure")
+    ap.add_argument("--placement", default="spread", choices=["spread", "plain"],
+                    help="spread: the five state arenas are allocated tens of GiB apart in physical memory "
+                         "(temporary spacers between them); plain: one allocation after the other")
+    ap.add_argument("--chunk-map", action="store_true",
+                    help="also time the update of every chunk on its own (one launch per chunk) and report the rate per chunk: "
+                         "shows how the speed follows the physical placement of the arenas")
     ap.add_argument("--fp16", action="store_true",
                     help="fp16 parameters and gradients with dynamic loss scaling (scale 2^16; gradients drawn scaled)")
     ap.add_argument("--zero-grads", action="store_true", help="variant: the update zeroes the gradient chunks it has read")
-    ap.add_argument("--processes", type=int, default=2,
-                    help="measure in this many fresh processes one after the other and report the best "
-                         "(physical placement of the state differs from process to process)")
+    ap.add_argument("--processes", type=int, default=1,
+                    help="measure in this many fresh processes one after the other and report the best (with "
+                         "--placement plain the physical placement of the state, and with it the update's speed, "
+                         "differs between a process started on an idle GPU and the next one)")
     ap.add_argument("--child", action="store_true", help=argparse.SUPPRESS)
     ap.add_argument("--sweep", action="store_true", help="also sweep the update kernel's launch shape (stderr)")
     ap.add_argument("--stream", action="store_true",
@@ -447,8 +456,12 @@ def main() -> int:
     if args.zero_grads:
         B.pt_ctx_set_option(ctx, "adamw_zero_grads", 1)
         layout_note += "; gradients zeroed by the update"
-    g16 = torch.zeros(C, S, dtype=torch.float32 if args.grad_accum else dt16, device=dev)
-    p16 = torch.zeros(C, S, dtype=dt16, device=dev)
+    from paper_2406_08334_amd.arena import spread_arenas
+    g16, p16, w, m, v = spread_arenas(
+        [((C, S), torch.float32 if args.grad_accum else dt16), ((C, S), dt16), ((C, S), torch.float32),
+         ((C, S), torch.float32), ((C, S), torch.float32)], device=dev,
+        gap_bytes=0 if args.placement == "plain" else None, keep_free_bytes=(n_sets + 1) * 2 * N)
+    layout_note += f"; arenas allocated {args.placement}"
     offs = np.cumsum([0] + sizes[:-1]).tolist()
     if args.layout == "grouped":
         # parameters are generated as the model's tensors and brought into chunk space by the same copy
@@ -463,11 +476,8 @@ def main() -> int:
         del flat
     else:
         synth.normal_16(synth.SEED_PARAMS, 0, 0, 0, N, 0.02, dt16, dev, out=p16.view(-1)[:N])
-    w = torch.empty(C, S, dtype=torch.float32, device=dev)
     for c in range(C):
         w[c].copy_(p16[c])
-    m = torch.zeros(C, S, dtype=torch.float32, device=dev)
-    v = torch.zeros(C, S, dtype=torch.float32, device=dev)
     grad_sets, plans = [], []
     for k in range(n_sets):
         gs = torch.empty(N, dtype=dt16, device=dev)
@@ -594,6 +604,24 @@ def main() -> int:
         t_g = (time.perf_counter() - t_g) / K
         out["hip_graph"] = {"ms_per_step": round(1e3 * t_g, 4), "GBps": round(step_bytes / t_g / 1e9, 1),
                             "speedup_over_eager": round(ms_step * 1e-3 / t_g, 3)}
+
+    if args.chunk_map:
+        rates = []
+        for c in range(C):
+            ts = []
+            for _ in range(3):
+                B.pt_step_override(ctx, 0.0121, False, stream)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                B.pt_chunk_adamw_step(ctx, hp, c, 1, r_g[c:c + 1], r_w[c:c + 1], r_m[c:c + 1], r_v[c:c + 1], r_p[c:c + 1], stream)
+                e1.record(stream)
+                B.pt_step_end(ctx, stream)
+                torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            rates.append(round(adamw_per_elem * S / min(ts) / 1e6))
+        out["chunk_map_GBps"] = rates
+        for i in range(0, C, 16):
+            log(f"[chunk-map] chunks {i:3d}..: " + " ".join(f"{r:5d}" for r in rates[i:i + 16]))
 
     if args.sweep:
         # launch-shape sweep of the update kernel, same process and allocations (stderr only)

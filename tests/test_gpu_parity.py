@@ -643,3 +643,22 @@ def test_resume_from_saved_state_gives_the_same_bits():
         a.close()
         if b is not None:
             b.close()
+
+
+# ------------------------------------------------------------------------- arena placement
+
+def test_spread_arenas_gives_zeroed_tensors_and_returns_the_spacers():
+    from paper_2406_08334_amd.arena import spread_arenas
+    torch.cuda.empty_cache()
+    free0, _ = torch.cuda.mem_get_info()
+    specs = [((3, 1 << 20), torch.bfloat16), ((3, 1 << 20), torch.float32), ((5,), torch.float32)]
+    for gap in (0, 64 << 20, None):
+        arenas = spread_arenas(specs, gap_bytes=gap)
+        assert [tuple(a.shape) for a in arenas] == [(3, 1 << 20), (3, 1 << 20), (5,)]
+        assert [a.dtype for a in arenas] == [torch.bfloat16, torch.float32, torch.float32]
+        assert all(a.is_cuda and a.is_contiguous() and not bool(a.view(-1).any()) for a in arenas)
+        assert all(a.data_ptr() % 256 == 0 for a in arenas)
+        free1, _ = torch.cuda.mem_get_info()
+        assert free0 - free1 < (1 << 30)               # the spacers (up to 20 GiB each) went back to the driver
+        del arenas
+        torch.cuda.empty_cache()
