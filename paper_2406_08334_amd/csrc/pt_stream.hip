@@ -17,16 +17,37 @@ static inline char* slot_v(const pt_ctx* c, uint32_t s) { return (char*)c->slot_
 static inline char* slot_grad(const pt_ctx* c, uint32_t s) { return (char*)c->slot_mem[s] + 12 * c->S; }
 static inline char* slot_p16(const pt_ctx* c, uint32_t s) { return (char*)c->slot_mem[s] + (12 + grad_bytes(c)) * c->S; }
 
+static int reserve_slots(pt_ctx* ctx, uint32_t n_slots);
+
+// Gives back whatever a failed reservation had already created, so that the call can be repeated.
+static void release_slots(pt_ctx* ctx) {
+  if (ctx->s_up) { (void)hipStreamDestroy(ctx->s_up); ctx->s_up = nullptr; }
+  if (ctx->s_comp) { (void)hipStreamDestroy(ctx->s_comp); ctx->s_comp = nullptr; }
+  if (ctx->s_down) { (void)hipStreamDestroy(ctx->s_down); ctx->s_down = nullptr; }
+  if (ctx->ev_fork) { (void)hipEventDestroy(ctx->ev_fork); ctx->ev_fork = nullptr; }
+  for (uint32_t s = 0; s < PT_MAX_SLOTS; ++s) {
+    if (ctx->ev_up[s]) { (void)hipEventDestroy(ctx->ev_up[s]); ctx->ev_up[s] = nullptr; }
+    if (ctx->ev_k[s]) { (void)hipEventDestroy(ctx->ev_k[s]); ctx->ev_k[s] = nullptr; }
+    if (ctx->ev_down[s]) { (void)hipEventDestroy(ctx->ev_down[s]); ctx->ev_down[s] = nullptr; }
+    if (ctx->slot_mem[s]) { (void)hipFree(ctx->slot_mem[s]); ctx->slot_mem[s] = nullptr; }
+  }
+}
+
 extern "C" int pt_stream_reserve(pt_ctx* ctx, uint32_t n_slots) {
   if (!ctx) return PT_ERR_INVALID_ARG;
   if (n_slots < 2 || n_slots > PT_MAX_SLOTS)
     return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_stream_reserve: n_slots must be in [2, %u]", PT_MAX_SLOTS);
   if (ctx->n_slots) return pt_fail(ctx, PT_ERR_STATE, "pt_stream_reserve: chunk buffers already reserved");
+  const int rc = reserve_slots(ctx, n_slots);
+  if (rc != PT_OK) release_slots(ctx);       // the error text set by the failing step stays
+  return rc;
+}
+
+static int reserve_slots(pt_ctx* ctx, uint32_t n_slots) {
   PT_HIP(ctx, hipStreamCreateWithFlags(&ctx->s_up, hipStreamNonBlocking));
   PT_HIP(ctx, hipStreamCreateWithFlags(&ctx->s_comp, hipStreamNonBlocking));
   PT_HIP(ctx, hipStreamCreateWithFlags(&ctx->s_down, hipStreamNonBlocking));
   PT_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming));
-  std::vector<uint64_t> cols(N_ROWS);
   for (uint32_t s = 0; s < n_slots; ++s) {
     PT_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_up[s], hipEventDisableTiming));
     PT_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_k[s], hipEventDisableTiming));
