@@ -70,6 +70,9 @@ def lib():
         L.orc_pack_dense.argtypes = [C.POINTER(u16p), u64p, C.c_uint32, C.c_uint64, u16p, C.c_uint64]
         L.orc_unpack_dense.restype = C.c_int64
         L.orc_unpack_dense.argtypes = [u16p, C.c_uint64, C.c_uint64, C.POINTER(u16p), u64p, C.c_uint32]
+        L.orc_pack_segments.restype = None
+        L.orc_pack_segments.argtypes = [C.POINTER(u16p), u64p, u64p, C.POINTER(C.c_uint32), u64p, C.c_uint32,
+                                        C.c_uint64, u16p]
         L.orc_found_nonfinite.restype = C.c_int32
         L.orc_found_nonfinite.argtypes = [u16p, C.c_uint64, C.c_int]
         L.orc_sqnorm.restype = C.c_double
@@ -152,6 +155,22 @@ def pack_dense(tensors, S: int, n_chunks: int | None = None) -> np.ndarray:
     if total == 0:
         chunks[...] = 0
     return chunks
+
+
+def pack_segments(segments, chunks: np.ndarray):
+    """segments: iterable of (tensor words, src_off, len, chunk, chunk_off); chunks: uint16 [C, S], changed in place."""
+    segs = [(np.ascontiguousarray(t, dtype=np.uint16).reshape(-1), int(so), int(n), int(c), int(co))
+            for t, so, n, c, co in segments]
+    assert chunks.dtype == np.uint16 and chunks.flags.c_contiguous and chunks.ndim == 2
+    C_, S = chunks.shape
+    for t, so, n, c, co in segs:
+        assert so + n <= t.size and c < C_ and co + n <= S
+    k = len(segs)
+    ptrs = (C.POINTER(C.c_uint16) * max(k, 1))(*[_u16(t) for t, *_ in segs])
+    arr = lambda vals, ct: (ct * max(k, 1))(*vals)
+    lib().orc_pack_segments(ptrs, arr([s[1] for s in segs], C.c_uint64), arr([s[2] for s in segs], C.c_uint64),
+                            arr([s[3] for s in segs], C.c_uint32), arr([s[4] for s in segs], C.c_uint64), k, S,
+                            _u16(chunks))
 
 
 def unpack_dense(chunks: np.ndarray, sizes) -> list:

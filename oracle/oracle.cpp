@@ -243,6 +243,17 @@ int64_t orc_pack_dense(const uint16_t* const* tensors, const uint64_t* elems, ui
   return int64_t(need);
 }
 
+// General form of the copy: segment i puts words [src_off, src_off + len) of its tensor into
+// chunk `chunk` at position chunk_off (the dense layout above is one such table; the paper's own
+// layout, which never splits a tensor, another).  Words no segment covers are left as they are.
+void orc_pack_segments(const uint16_t* const* src, const uint64_t* src_off, const uint64_t* len,
+                       const uint32_t* chunk, const uint64_t* chunk_off, uint32_t n_segs, uint64_t S,
+                       uint16_t* chunks) {
+  for (uint32_t i = 0; i < n_segs; ++i)
+    for (uint64_t j = 0; j < len[i]; ++j)
+      chunks[uint64_t(chunk[i]) * S + chunk_off[i] + j] = src[i][src_off[i] + j];
+}
+
 int64_t orc_unpack_dense(const uint16_t* chunks, uint64_t S, uint64_t n_chunks,
                          uint16_t* const* tensors, const uint64_t* elems, uint32_t n_tensors) {
   uint64_t e = 0;

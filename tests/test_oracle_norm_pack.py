@@ -158,3 +158,34 @@ def test_found_nonfinite(orc):
         assert orc.found_nonfinite(h, orc.FP16)
     h = f.copy(); h[0] = 0x7BFF                       # 65504
     assert not orc.found_nonfinite(h, orc.FP16)
+
+
+def test_segment_copy_against_brute_force_and_the_dense_layout(orc):
+    """general segment table: per-element Python loops on a tiny case; with the dense layout's own
+    table (e -> (e div S, e mod S), written out here) it must reproduce pack_dense"""
+    rng = np.random.default_rng(17)
+    tensors = [rng.integers(0, 1 << 16, n, dtype=np.uint16) for n in (5, 1, 12, 7)]
+    table = [(2, 3, 4, 1, 9), (0, 0, 5, 0, 2), (3, 1, 6, 1, 0), (2, 0, 3, 0, 13), (1, 0, 1, 2, 15)]   # tensor, src_off, len, chunk, off
+    chunks = np.full((3, 16), 0xBEEF, np.uint16)
+    want = chunks.copy()
+    for t, so, n, c, co in table:
+        for j in range(n):
+            want[c, co + j] = tensors[t][so + j]
+    orc.pack_segments([(tensors[t], so, n, c, co) for t, so, n, c, co in table], chunks)
+    assert np.array_equal(chunks, want) and (chunks == 0xBEEF).sum() == 48 - 19
+    # dense table, cut wherever a tensor crosses a chunk boundary
+    sizes, S = [1, 3, 7, 8, 9, 17, 40, 2], 16
+    ts = [rng.integers(0, 1 << 16, n, dtype=np.uint16) for n in sizes]
+    segs, e = [], 0
+    for t in ts:
+        done = 0
+        while done < t.size:
+            c, pos = (e + done) // S, (e + done) % S
+            n = min(S - pos, t.size - done)
+            segs.append((t, done, n, c, pos))
+            done += n
+        e += t.size
+    dense = orc.pack_dense(ts, S)
+    out = np.zeros_like(dense)
+    orc.pack_segments(segs[::-1], out)                                   # order of the table does not matter
+    assert np.array_equal(out, dense)
