@@ -174,3 +174,12 @@ def test_context_creation_without_a_gpu_is_an_error_code_not_a_crash():
     assert not out.value and "hipGetDevice" in B.pt_last_error(None)
     with pytest.raises(B.PtError):
         B.pt_ctx_create(B.PT_BF16, 64, 1)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """the benchmark is a one-GPU program: --gpus above 1 exits with a message, before any GPU work"""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode == 2 and "ONE GPU" in res.stderr and res.stdout.strip() == ""
