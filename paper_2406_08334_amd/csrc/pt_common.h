@@ -8,6 +8,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <new>
 #include <string>
 #include <vector>
 
@@ -131,7 +132,20 @@ struct pt_ctx {
 };
 
 // ---- error plumbing ----------------------------------------------------------------
-int pt_fail(pt_ctx* ctx, int status, const char* fmt, ...);
+int pt_fail(pt_ctx* ctx, int status, const char* fmt, ...) noexcept;
+
+// Runs the body of an entry point that allocates host memory; a C++ exception becomes a status
+// code, so that nothing is ever thrown across the C boundary.
+template <class F>
+inline int pt_guarded(pt_ctx* ctx, const char* who, F&& body) noexcept {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    return pt_fail(ctx, PT_ERR_NOMEM, "%s: out of host memory", who);
+  } catch (...) {
+    return pt_fail(ctx, PT_ERR_UNSUPPORTED, "%s: unexpected C++ exception", who);
+  }
+}
 
 #define PT_HIP(ctx, call)                                                              \
   do {                                                                                 \

@@ -8,13 +8,17 @@
 
 static thread_local std::string g_noctx_error;
 
-int pt_fail(pt_ctx* ctx, int status, const char* fmt, ...) {
+int pt_fail(pt_ctx* ctx, int status, const char* fmt, ...) noexcept {
   char buf[512];
   va_list ap;
   va_start(ap, fmt);
   vsnprintf(buf, sizeof buf, fmt, ap);
   va_end(ap);
-  if (ctx) ctx->err = buf; else g_noctx_error = buf;
+  try {
+    if (ctx) ctx->err = buf; else g_noctx_error = buf;
+  } catch (...) {
+    // no memory even for the text: the status code still says what happened
+  }
   return status;
 }
 
@@ -166,9 +170,9 @@ extern "C" int pt_ctx_create(pt_ctx** out, int dtype, uint64_t chunk_elems, uint
   ctx->norm_blocks = uint32_t((chunk_elems + PT_NORM_BLOCK_ELEMS - 1) / PT_NORM_BLOCK_ELEMS);
   ctx->table_cols = n_chunks + PT_MAX_SLOTS;
   ctx->scaler = scaler != nullptr;
-  int rc = ctx_alloc(ctx, scaler);
+  int rc = pt_guarded(ctx, "pt_ctx_create", [&] { return ctx_alloc(ctx, scaler); });
   if (rc != PT_OK) {
-    g_noctx_error = ctx->err;
+    try { g_noctx_error = ctx->err; } catch (...) {}
     ctx_free_all(ctx);
     delete ctx;
     return rc;
@@ -235,9 +239,15 @@ extern "C" int pt_ctx_set_option(pt_ctx* ctx, const char* name, int64_t value) {
   return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_ctx_set_option: unknown option '%s'", name);
 }
 
+static int set_no_decay(pt_ctx* ctx, const pt_segment* segs, uint32_t n_segs);
+
 extern "C" int pt_ctx_set_no_decay(pt_ctx* ctx, const pt_segment* segs, uint32_t n_segs) {
   if (!ctx) return PT_ERR_INVALID_ARG;
   if (!segs && n_segs) return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_ctx_set_no_decay: segs is NULL");
+  return pt_guarded(ctx, "pt_ctx_set_no_decay", [&] { return set_no_decay(ctx, segs, n_segs); });
+}
+
+static int set_no_decay(pt_ctx* ctx, const pt_segment* segs, uint32_t n_segs) {
   // per chunk: sort, merge touching ranges
   std::vector<std::vector<std::pair<uint64_t, uint64_t>>> per(ctx->C);
   for (uint32_t i = 0; i < n_segs; ++i) {

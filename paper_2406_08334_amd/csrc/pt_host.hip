@@ -181,8 +181,8 @@ extern "C" int pt_chunk_host_adamw_step(pt_ctx* ctx, const pt_hparams* hp, uint3
   };
   std::vector<std::thread> pool;
   const uint32_t extra = n_threads - 1;
-  pool.reserve(extra);
   try {
+    pool.reserve(extra);
     for (uint32_t t = 0; t < extra; ++t) pool.emplace_back(worker);
   } catch (...) {
     // could not start every thread: the shared work queue is drained by those that did start

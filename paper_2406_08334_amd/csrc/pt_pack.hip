@@ -13,6 +13,7 @@
 #include <hip/hip_fp16.h>
 
 #include <algorithm>
+#include <memory>
 
 namespace {
 
@@ -165,10 +166,16 @@ static void plan_free(pt_pack_plan* p) {
   if (p->d_tile_flag) (void)hipFree(p->d_tile_flag);
 }
 
+static int plan_create(pt_ctx* ctx, const pt_segment* segs, uint32_t n_segs, pt_pack_plan** out);
+
 extern "C" int pt_pack_plan_create(pt_ctx* ctx, const pt_segment* segs, uint32_t n_segs, pt_pack_plan** out) {
   if (!ctx) return PT_ERR_INVALID_ARG;
   if (!out || (!segs && n_segs)) return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_pack_plan_create: NULL argument");
   *out = nullptr;
+  return pt_guarded(ctx, "pt_pack_plan_create", [&] { return plan_create(ctx, segs, n_segs, out); });
+}
+
+static int plan_create(pt_ctx* ctx, const pt_segment* segs, uint32_t n_segs, pt_pack_plan** out) {
   // validate: inside chunks, sources present and 2-byte aligned, no overlap inside a chunk
   std::vector<uint32_t> order(n_segs);
   for (uint32_t i = 0; i < n_segs; ++i) {
@@ -221,11 +228,13 @@ extern "C" int pt_pack_plan_create(pt_ctx* ctx, const pt_segment* segs, uint32_t
 
   pt_pack_plan* p = new (std::nothrow) pt_pack_plan();
   if (!p) return pt_fail(ctx, PT_ERR_NOMEM, "pt_pack_plan_create: out of host memory");
+  std::unique_ptr<pt_pack_plan> hold(p);            // freed on every early return and on an exception
   p->ctx = ctx; p->n_tiles = uint32_t(tiles.size()); p->total_elems = total;
   for (uint32_t c = 0; c < ctx->C; ++c)
     if (begin[c + 1] > begin[c]) p->touched.push_back(c);
   auto bail = [&](hipError_t e, const char* what) {
-    plan_free(p); delete p;
+    plan_free(p);
+    p->d_tiles = nullptr; p->d_chunk_tile_begin = nullptr; p->d_tile_sq = nullptr; p->d_tile_flag = nullptr;
     return pt_fail(ctx, PT_ERR_HIP, "pt_pack_plan_create: %s failed: %s", what, hipGetErrorString(e));
   };
   hipError_t e;
@@ -239,7 +248,7 @@ extern "C" int pt_pack_plan_create(pt_ctx* ctx, const pt_segment* segs, uint32_t
     return bail(e, "hipMemcpy(tiles)");
   if ((e = hipMemcpy(p->d_chunk_tile_begin, begin.data(), begin.size() * sizeof(uint32_t), hipMemcpyHostToDevice)) != hipSuccess)
     return bail(e, "hipMemcpy(begin)");
-  *out = p;
+  *out = hold.release();
   return PT_OK;
 }
 
