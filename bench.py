@@ -353,7 +353,7 @@ def main() -> int:
     ap.add_argument("--workload", default="llama_7b", help="llama_7b | gpt2_xl | gpt2_block_768")
     ap.add_argument("--grad-sets", type=int, default=3, help="distinct pre-generated gradient sets, rotated")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-chunks", type=int, default=4)
+    ap.add_argument("--cpu-sample-chunks", type=int, default=24)
     ap.add_argument("--calib", action="store_true", help="also time a bare copy kernel (attainable HBM rate)")
     ap.add_argument("--layout", default="dense", choices=["dense", "grouped"],
                     help="dense: the benchmark configurations' layout; grouped: the paper's no-split, block-per-chunk layout")
@@ -665,7 +665,7 @@ def main() -> int:
         n_el = n_cpu * S
         ow, om, ov, op = cpu_in["w"], np.zeros(n_el, np.float32), np.zeros(n_el, np.float32), cpu_in["p"]
         ost = O.new_state(None)
-        reps = 2
+        reps = 3
         t_cpu = time.perf_counter()
         for _ in range(reps):
             chunks = O.pack_dense(cpu_in["src"], S, n_chunks=n_cpu)
