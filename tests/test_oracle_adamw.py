@@ -372,3 +372,42 @@ def test_no_decay_mask_closed_form_and_library_pin(orc):
         opt.step()
     wt = np.empty(n); wt[idx_d] = pd.detach().numpy(); wt[idx_n] = pn.detach().numpy()
     assert np.all(np.abs(wa - wt) <= 1e-6 * trk.W)
+
+
+def test_f32_sequence_is_exact_where_every_operation_is_exact(orc):
+    """A case built so that no operation of the fp32 sequence rounds: powers of two for the
+    hyper-parameters, gradients of one magnitude equal to eps, small dyadic weights, first step.
+    Then the sequence, the fp64 evaluation and exact rational arithmetic must agree bit for bit;
+    a dropped, doubled or mis-signed term anywhere in the sequence breaks the equality."""
+    from fractions import Fraction as F
+    n = 4096
+    rng = np.random.default_rng(7)
+    h = hp(lr=2.0 ** -10, beta1=0.5, beta2=0.75, eps=2.0 ** -10, weight_decay=0.5, max_norm=0.0)
+    gm = 2.0 ** -3
+    sign = rng.choice([-1.0, 1.0], n)
+    g16 = bf16w(sign * 2.0 ** -7)                                   # g = +-2^-7 * 2^-3 = +-2^-10 = +-eps
+    j = rng.integers(-1000, 1001, n)
+    w0 = (j * 2.0 ** -6).astype(np.float32)
+    states = []
+    for fn in ("f64", "f32"):
+        w, m, v, p16 = w0.copy(), np.zeros(n, np.float32), np.zeros(n, np.float32), np.zeros(n, np.uint16)
+        if fn == "f64":
+            orc.adamw_f64(h, 1, gm, g16, w, m, v, p16, orc.BF16)
+        else:
+            c = orc.consts_f32(h, 1, gm)
+            # the nine constants themselves are exact here
+            assert [F(float(x)) for x in c] == [F(1, 2), F(3, 4), F(1, 2), F(1, 4), 1 - F(1, 2 ** 11), F(1, 2 ** 9), F(2),
+                                                F(1, 2 ** 10), F(1, 8)]
+            orc.adamw_f32seq(c, g16, w, m, v, p16, orc.BF16)
+        states.append((w, m, v, p16))
+    for a, b in zip(*states):
+        assert a.tobytes() == b.tobytes()
+    w, m, v, p16 = states[1]
+    for i in range(0, n, 37):                                        # exact rationals, element by element
+        g = F(float(sign[i])) * F(1, 2 ** 10)
+        assert F(float(m[i])) == g / 2                                # (1 - beta1) g
+        assert F(float(v[i])) == g * g / 4                            # (1 - beta2) g^2
+        d = abs(g) / 2 * 2 + F(1, 2 ** 10)                            # sqrt(v) / sqrt(1 - beta2) + eps = 2^-9
+        want = F(int(j[i]), 64) * (1 - F(1, 2 ** 11)) - F(1, 2 ** 9) * ((g / 2) / d)
+        assert F(float(w[i])) == want
+    assert np.array_equal(p16, orc.encode16_rne(w, orc.BF16))
