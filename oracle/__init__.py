@@ -14,8 +14,11 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "oracle.cpp")
-_LIB = os.path.join(_HERE, "liboracle.so")
+# ORACLE_SRC_OVERRIDE: build and load another source file instead (tests/oracle_mutation_check.py
+# points it at copies of oracle.cpp with one planted mistake each, to see the pins catch it)
+_OVERRIDE = os.environ.get("ORACLE_SRC_OVERRIDE")
+_SRC = _OVERRIDE or os.path.join(_HERE, "oracle.cpp")
+_LIB = (os.path.splitext(_OVERRIDE)[0] + ".so") if _OVERRIDE else os.path.join(_HERE, "liboracle.so")
 
 BF16, FP16 = 0, 1
 
