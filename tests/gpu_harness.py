@@ -116,6 +116,13 @@ class ChunkedState:
             mask[s.chunk * self.S + s.chunk_off: s.chunk * self.S + s.chunk_off + s.len] = 1
         return mask
 
+    def oracle_packed(self, orc):
+        """the source gradients packed by the ORACLE (dense layout), flat over [C * S]: what the oracle is
+        fed, so that none of its inputs has passed through the HIP path"""
+        src = to_u16(self.grad_src[:self.N]) if self.N else np.zeros(0, np.uint16)
+        offs = np.cumsum([0] + self.sizes)
+        return orc.pack_dense([src[offs[i]:offs[i + 1]] for i in range(len(self.sizes))], self.S, self.C).reshape(-1)
+
     # ---- host copies for the oracle
     def host_state(self):
         torch.cuda.synchronize()

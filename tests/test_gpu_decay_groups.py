@@ -45,8 +45,11 @@ def test_masked_kernel_is_bit_exact_against_the_masked_f32_sequence(orc, dtype, 
             st.adamw(hp_b)
             k = B.pt_update_consts_read(st.ctx)
             st.end()
-            consts = np.array(list(k.c), dtype=np.float32)
-            host["g16"] = plain["g16"] = to_u16(st.g16).reshape(-1).copy()
+            consts = orc.consts_f32(hp_o, t, float(np.float32(0.0121)))
+            assert same_bits(np.array(list(k.c), dtype=np.float32), consts)      # the oracle runs on its own constants
+            g16 = orc.pack_dense([to_u16(st.grad_src[:st.N])], S, st.C).reshape(-1)     # ... and its own packing
+            assert_same_bits(to_u16(st.g16).reshape(-1), g16, ("g16", t))
+            host["g16"] = plain["g16"] = g16.copy()
             run_oracle_f32seq(orc, consts, host, st.orc_dtype, no_decay=mask)
             run_oracle_f32seq(orc, consts, plain, st.orc_dtype)
             got = st.host_state()

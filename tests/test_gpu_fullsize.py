@@ -234,12 +234,25 @@ def run_full(workload, dtype, steps, scaler_b=None, scaler_o=None, inf_step=None
             if scaler_o is not None:
                 ost.good_steps += 1
             assert after.step == ost.t and after.loss_scale == ost.loss_scale
-            consts = np.array(list(k.c), dtype=np.float32)
-            assert np.abs(consts.view(np.int32).astype(np.int64) -
-                          O.consts_f32(hp_o, ost.t, gm).view(np.int32).astype(np.int64)).max() <= 1
+            # The fp32 sequence runs on the oracle's own constants.  Eight of the nine do not depend on the norm
+            # and must equal the device's bit for bit; grad_mult does, and the oracle's one-after-the-other fp64
+            # sum of 6.7e9 squares is itself only good to ~1e-10, so once in a thousand steps its fp32 rounding
+            # may land on the neighbouring value: then (and only then) the device's grad_mult is taken.
+            dev_c = np.array(list(k.c), dtype=np.float32)
+            consts = O.consts_f32(hp_o, ost.t, gm)
+            assert consts[:8].tobytes() == dev_c[:8].tobytes()
+            assert abs(int(consts[8:].view(np.int32)[0]) - int(dev_c[8:].view(np.int32)[0])) <= 1
+            if consts[8] != dev_c[8]:
+                print(f"[fullsize] step {s}: grad_mult one ulp apart, taking the device's", flush=True)
+                consts[8] = dev_c[8]
             for c in sample:
                 got = st.chunk_host(c)
                 sh = shadow[c]
+                # the chunk's gradients as the dense layout defines them, from the seeded source itself
+                src = to_u16(st.grad_src[c * S: min(N, (c + 1) * S)])
+                want_g = np.zeros(S, np.uint16); want_g[:src.size] = src
+                assert_same_bits(got["g16"], want_g, ("g16", c, s))
+                got["g16"] = want_g
                 sh["f32"]["g16"] = got["g16"]
                 O.adamw_f32seq(consts, got["g16"], sh["f32"]["w"], sh["f32"]["m"], sh["f32"]["v"], sh["f32"]["p16"],
                                st.orc_dtype, threads=16)

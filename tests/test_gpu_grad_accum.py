@@ -21,9 +21,7 @@ SCALER_B = B.pt_scaler_cfg(65536.0, 2.0, 0.5, 2000, 0)
 
 def flat_words(orc, st):
     """the micro-batch's source words laid out as the chunks' flat concatenation (oracle pack)"""
-    src = to_u16(st.grad_src[:st.N]) if st.N else np.zeros(0, np.uint16)
-    offs = np.cumsum([0] + st.sizes)
-    return orc.pack_dense([src[offs[i]:offs[i + 1]] for i in range(len(st.sizes))], st.S, st.C).reshape(-1)
+    return st.oracle_packed(orc)
 
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
@@ -107,16 +105,21 @@ def test_update_from_fp32_gradients_is_bit_exact_against_the_f32_sequence(orc, d
         trk = ScaleTracker(host["w"], host["m"], hpd)
         gm = 0.0121
         for t in (1, 2, 3):
+            g32 = np.zeros(st.C * S, np.float32)
             for k in range(2):
                 st.set_grads(t, micro=k)
                 st.accum(overwrite=(k == 0), take_norm=False)
-            g32 = st.host_state()["g32"]
+                part = g32[:st.N].copy()                          # the oracle accumulates the same sources itself
+                orc.accum_f32(flat_words(orc, st)[:st.N], part, st.orc_dtype, overwrite=(k == 0))
+                g32[:st.N] = part
+            assert_same_bits(st.host_state()["g32"], g32, ("g32", t))
             assert not np.array_equal(orc.decode16(orc.encode16_rne(g32, st.orc_dtype), st.orc_dtype), g32)
             B.pt_step_override(st.ctx, gm, False)
             st.adamw(hp_b)
             k_ = B.pt_update_consts_read(st.ctx)
             st.end()
-            consts = np.array(list(k_.c), dtype=np.float32)
+            consts = orc.consts_f32(hp_o, t, float(np.float32(gm)))
+            assert same_bits(np.array(list(k_.c), dtype=np.float32), consts)    # the oracle runs on its own constants
             orc.adamw_f32seq_g32(consts, g32, host["w"], host["m"], host["v"], host["p16"], st.orc_dtype, threads=8,
                                  no_decay=mask)
             got = st.host_state()
@@ -179,18 +182,23 @@ def end_to_end_accum(orc, sizes, S, dtype, steps, micro, scaler_b=None, scaler_o
         reps = []
         for s in range(1, steps + 1):
             sigma = ost.loss_scale
+            g32 = np.zeros(st.C * S, np.float32)
             for k in range(micro):
                 st.set_grads(s, std=1e-3, scale=sigma, micro=k)
                 if inf_at == (s, k):
                     st.grad_src.view(torch.int16)[st.N // 3] = 0x7C00 if dtype == torch.float16 else 0x7F80
                 st.accum(overwrite=(k == 0), take_norm=(k == micro - 1))
+                part = g32[:st.N].copy()                          # the oracle accumulates the same sources itself
+                orc.accum_f32(st.oracle_packed(orc)[:st.N], part, st.orc_dtype, overwrite=(k == 0))
+                g32[:st.N] = part
             st.norm()
             st.adamw(hp_b)
             rep = B.pt_step_report_read(st.ctx)
             k_ = B.pt_update_consts_read(st.ctx)
             st.end()
             got = st.host_state()
-            g32 = got["g32"]
+            same = (got["g32"].view(np.uint32) == g32.view(np.uint32)) | (np.isnan(got["g32"]) & np.isnan(g32))
+            assert same.all()
             orep = orc.step_g32(hp_o, scaler_o, ost, g32, host["w"], host["m"], host["v"], host["p16"], S, st.orc_dtype,
                                 threads=8, no_decay=mask)
             reps.append((rep, orep))
@@ -209,7 +217,8 @@ def end_to_end_accum(orc, sizes, S, dtype, steps, micro, scaler_b=None, scaler_o
             far = check_p16(orc.decode16(got["p16"], st.orc_dtype), orc.decode16(host["p16"], st.orc_dtype),
                             host["w"], trk.W, dtype == torch.float16)
             assert far <= 1e-4 * got["p16"].size
-            consts = np.array(list(k_.c), dtype=np.float32)
+            consts = orc.consts_f32(hp_o, ost.t, orep.grad_mult)            # the oracle's own constants
+            assert same_bits(np.array(list(k_.c), dtype=np.float32), consts)
             orc.adamw_f32seq_g32(consts, g32, fa["w"], fa["m"], fa["v"], fa["p16"], st.orc_dtype, threads=8, no_decay=mask)
             for name in ("w", "m", "v", "p16"):
                 assert_same_bits(got[name], fa[name], (name, s))

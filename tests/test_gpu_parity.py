@@ -174,11 +174,13 @@ def test_adamw_kernel_isolated_is_bit_exact_against_f32_sequence(orc, dtype, S, 
             st.end()
             consts = np.array(list(k.c), dtype=np.float32)
             want_c = orc.consts_f32(hp_o, t, float(np.float32(gm)))
-            assert ulp_diff32(consts, want_c).max() <= 1 and k.skip == 0
-            assert consts[8] == np.float32(gm)
-            g16 = to_u16(st.g16).reshape(-1)
+            # the device derives the very constants the oracle derives: the oracle runs on its own
+            assert same_bits(consts, want_c) and k.skip == 0
+            # ... and on its own packing of the same seeded source gradients
+            g16 = orc.pack_dense([to_u16(st.grad_src[:st.N])], S, st.C).reshape(-1)
+            assert_same_bits(to_u16(st.g16).reshape(-1), g16, ("g16", t))
             host["g16"] = g16.copy()
-            run_oracle_f32seq(orc, consts, host, st.orc_dtype)
+            run_oracle_f32seq(orc, want_c, host, st.orc_dtype)
             got = st.host_state()
             for name in ("w", "m", "v", "p16"):
                 assert same_bits(got[name], host[name]), (name, t)
@@ -245,7 +247,8 @@ def end_to_end(orc, sizes, S, dtype, steps, grad_std=1e-3, scaler_b=None, scaler
             rep = B.pt_step_report_read(st.ctx)
             k = B.pt_update_consts_read(st.ctx)
             st.end()
-            g16 = to_u16(st.g16).reshape(-1).copy()
+            g16 = st.oracle_packed(orc)                              # the oracle packs the seeded sources itself
+            assert_same_bits(to_u16(st.g16).reshape(-1), g16, ("g16", s))
             orep = orc.step(hp_o, scaler_o, ost, g16, host["w"], host["m"], host["v"], host["p16"], S,
                             st.orc_dtype, threads=8, no_decay=mask)
             reports.append((rep, orep))
@@ -268,7 +271,10 @@ def end_to_end(orc, sizes, S, dtype, steps, grad_std=1e-3, scaler_b=None, scaler
             far = check_p16(orc.decode16(got["p16"], st.orc_dtype), orc.decode16(host["p16"], st.orc_dtype),
                             host["w"], trk.W, dtype == torch.float16)
             assert far <= 1e-4 * got["p16"].size          # beyond one ulp only where w's terms cancel
-            consts = np.array(list(k.c), dtype=np.float32)
+            # the oracle's own norm gives the very constants the device derived (the two norms agree to
+            # 1e-15, far inside the fp32 rounding of grad_mult), so the fp32 sequence runs on the oracle's
+            consts = orc.consts_f32(hp_o, ost.t, orep.grad_mult)
+            assert same_bits(np.array(list(k.c), dtype=np.float32), consts)
             fa["g16"] = g16
             run_oracle_f32seq(orc, consts, fa, st.orc_dtype, no_decay=mask)
             for name in ("w", "m", "v", "p16"):
@@ -592,7 +598,8 @@ def test_hyper_parameter_corners_end_to_end(orc, kw):
             rep = B.pt_step_report_read(st.ctx)
             k = B.pt_update_consts_read(st.ctx)
             st.end()
-            g16 = to_u16(st.g16).reshape(-1).copy()
+            g16 = st.oracle_packed(orc)
+            assert_same_bits(to_u16(st.g16).reshape(-1), g16, ("g16", s))
             orep = orc.step(hp_o, None, ost, g16, host["w"], host["m"], host["v"], host["p16"], st.S, orc.BF16, threads=4)
             assert abs(rep.clip_coef - orep.clip_coef) <= 1e-12 * orep.clip_coef
             if hpd["max_norm"] <= 0 or hpd["max_norm"] > 1e6:
@@ -600,8 +607,10 @@ def test_hyper_parameter_corners_end_to_end(orc, kw):
             got = st.host_state()
             trk.advance(s, orc.decode16(g16, orc.BF16).astype(np.float64) * orep.grad_mult, host["v"])
             trk.check((got["w"], got["m"], got["v"]), (host["w"], host["m"], host["v"]), tol=1e-6)
+            consts = orc.consts_f32(hp_o, ost.t, orep.grad_mult)            # the oracle's own constants
+            assert same_bits(np.array(list(k.c), dtype=np.float32), consts)
             fa["g16"] = g16
-            run_oracle_f32seq(orc, np.array(list(k.c), dtype=np.float32), fa, orc.BF16)
+            run_oracle_f32seq(orc, consts, fa, orc.BF16)
             for name in ("w", "m", "v", "p16"):
                 assert_same_bits(got[name], fa[name], (name, s, kw))
     finally:

@@ -144,18 +144,14 @@ def test_forty_steps_with_loss_scale_events_stay_bit_exact(orc):
             rep = B.pt_step_report_read(st.ctx)
             k = B.pt_update_consts_read(st.ctx)
             st.end()
-            g16 = to_u16(st.g16).reshape(-1).copy()
-            want_inf = orc.found_nonfinite(g16, orc.FP16)
-            assert rep.found_inf == int(want_inf) == int(s % 7 == 0) and rep.loss_scale == sigma
-            if want_inf:
-                ost.loss_scale = max(sigma * 0.5, 1.0); ost.good_steps = 0
-            else:
-                ost.t += 1
-                orc.adamw_f32seq(np.array(list(k.c), np.float32), g16, host["w"], host["m"], host["v"], host["p16"],
-                                 orc.FP16, threads=4)
-                ost.good_steps += 1
-                if ost.good_steps >= so.growth_interval:
-                    ost.loss_scale = sigma * 2.0; ost.good_steps = 0
+            g16 = st.oracle_packed(orc)                              # the oracle packs the seeded sources itself
+            assert_same_bits(to_u16(st.g16).reshape(-1), g16, ("g16", s))
+            # the whole step in the oracle, fp32 sequence, its own norm, constants and loss-scale machine
+            orep = orc.step(hp_o, so, ost, g16, host["w"], host["m"], host["v"], host["p16"], st.S, orc.FP16,
+                            use_f32seq=True, threads=4)
+            assert rep.found_inf == orep.found_inf == int(s % 7 == 0) and rep.loss_scale == orep.loss_scale_used == sigma
+            if not orep.found_inf:
+                assert same_bits(np.array(list(k.c), np.float32), orc.consts_f32(hp_o, ost.t, orep.grad_mult))
             after = B.pt_step_report_read(st.ctx)
             assert (after.step, after.loss_scale, after.good_steps) == (ost.t, ost.loss_scale, ost.good_steps), s
             got = st.host_state()
