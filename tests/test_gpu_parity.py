@@ -93,7 +93,8 @@ def test_norm_fused_and_standalone_match_oracle(orc, dtype, scaler, sizes, S):
         st.set_grads(1, scale=sigma)
         st.pack(); st.norm()
         r1 = st.report()
-        g = to_u16(st.g16).reshape(-1)
+        g = st.oracle_packed(orc)                                    # the oracle's own packing of the sources
+        assert_same_bits(to_u16(st.g16).reshape(-1), g, "g16")
         want = orc.sqnorm(g, st.orc_dtype, loss_scale=sigma, block=S, threads=8)
         assert r1.found_inf == 0
         assert abs(r1.sqnorm - want) <= 1e-12 * want                 # bar is 1e-5 on the norm
