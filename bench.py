@@ -457,10 +457,21 @@ def main() -> int:
         B.pt_ctx_set_option(ctx, "adamw_zero_grads", 1)
         layout_note += "; gradients zeroed by the update"
     from paper_2406_08334_amd.arena import spread_arenas
-    g16, p16, w, m, v = spread_arenas(
-        [((C, S), torch.float32 if args.grad_accum else dt16), ((C, S), dt16), ((C, S), torch.float32),
-         ((C, S), torch.float32), ((C, S), torch.float32)], device=dev,
-        gap_bytes=0 if args.placement == "plain" else None, keep_free_bytes=(n_sets + 1) * 2 * N)
+    # One allocation pass places everything that the timed kernels stream: the five state arenas, then the
+    # source gradient sets (so that pack reads from another part of the memory than it writes to).  fp32
+    # gradient chunks are read, added to and written back by one kernel: their arena is cut in two halves, the
+    # second allocated last, so that the accumulate kernel's two tile streams fall on distant memory.
+    g_dtype = torch.float32 if args.grad_accum else dt16
+    C_lo = C // 2 if args.grad_accum and args.placement == "spread" else C
+    specs = [((C_lo, S), g_dtype), ((C, S), dt16), ((C, S), torch.float32), ((C, S), torch.float32),
+             ((C, S), torch.float32)] + [((N,), dt16)] * n_sets
+    if C_lo < C:
+        specs.append(((C - C_lo, S), g_dtype))
+    arenas = spread_arenas(specs, device=dev, gap_bytes=0 if args.placement == "plain" else None,
+                           keep_free_bytes=2 * N if args.layout == "grouped" else 0)
+    g16, p16, w, m, v = arenas[:5]
+    grad_set_mem = arenas[5:5 + n_sets]
+    g_hi = arenas[-1] if C_lo < C else None
     layout_note += f"; arenas allocated {args.placement}"
     offs = np.cumsum([0] + sizes[:-1]).tolist()
     if args.layout == "grouped":
@@ -480,7 +491,7 @@ def main() -> int:
         w[c].copy_(p16[c])
     grad_sets, plans = [], []
     for k in range(n_sets):
-        gs = torch.empty(N, dtype=dt16, device=dev)
+        gs = grad_set_mem[k]
         synth.normal_16(synth.SEED_GRADS, k + 1, 0, 0, N, 1e-3, dt16, dev, scale=sigma, outlier_every=outlier_every, out=gs)
         for s in segs:
             s.src = gs.data_ptr() + 2 * offs[s.tensor]
@@ -491,7 +502,9 @@ def main() -> int:
 
     hp = B.hparams(**HP)
     rows = lambda a: [a[c] for c in range(C)]
-    r_g, r_w, r_m, r_v, r_p = rows(g16), rows(w), rows(m), rows(v), rows(p16)
+    r_g, r_w, r_m, r_v, r_p = [g16[c] for c in range(C_lo)], rows(w), rows(m), rows(v), rows(p16)
+    if g_hi is not None:
+        r_g += [g_hi[c] for c in range(C - C_lo)]
     stream = torch.cuda.current_stream()
 
     # ---- CPU baseline input: the sample chunks' state BEFORE any step (oracle runs afterwards)
