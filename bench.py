@@ -457,20 +457,19 @@ def main() -> int:
         B.pt_ctx_set_option(ctx, "adamw_zero_grads", 1)
         layout_note += "; gradients zeroed by the update"
     from paper_2406_08334_amd.arena import spread_arenas
-    # One allocation pass places everything that the timed kernels stream: the five state arenas, then the
-    # source gradient sets (so that pack reads from another part of the memory than it writes to).  fp32
-    # gradient chunks are read, added to and written back by one kernel: their arena is cut in two halves, the
-    # second allocated last, so that the accumulate kernel's two tile streams fall on distant memory.
+    # The five state arenas are spread over the physical memory (see arena.py).  fp32 gradient chunks are read,
+    # added to and written back by one kernel: their arena is cut in two halves, the second allocated last,
+    # behind the source gradient sets, so that the accumulate kernel's two tile streams fall on distant memory.
     g_dtype = torch.float32 if args.grad_accum else dt16
     C_lo = C // 2 if args.grad_accum and args.placement == "spread" else C
     specs = [((C_lo, S), g_dtype), ((C, S), dt16), ((C, S), torch.float32), ((C, S), torch.float32),
-             ((C, S), torch.float32)] + [((N,), dt16)] * n_sets
+             ((C, S), torch.float32)]
     if C_lo < C:
-        specs.append(((C - C_lo, S), g_dtype))
+        specs += [((N,), dt16)] * n_sets + [((C - C_lo, S), g_dtype)]
     arenas = spread_arenas(specs, device=dev, gap_bytes=0 if args.placement == "plain" else None,
-                           keep_free_bytes=2 * N if args.layout == "grouped" else 0)
+                           keep_free_bytes=(2 * N if args.layout == "grouped" else 0) + (0 if C_lo < C else 2 * N * n_sets))
     g16, p16, w, m, v = arenas[:5]
-    grad_set_mem = arenas[5:5 + n_sets]
+    grad_set_mem = arenas[5:5 + n_sets] if C_lo < C else [torch.empty(N, dtype=dt16, device=dev) for _ in range(n_sets)]
     g_hi = arenas[-1] if C_lo < C else None
     layout_note += f"; arenas allocated {args.placement}"
     offs = np.cumsum([0] + sizes[:-1]).tolist()
