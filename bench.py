@@ -31,7 +31,7 @@ PACK_BYTES_PER_ELEM = 4            # read 2 + write 2
 # HBM traffic of one AdamW launch from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by the
 # same counters on pt_calib_copy); filled from the summaries under profiles/.  bytes per launch.
 MEASURED_TRAFFIC = {
-    # profiles/k_adamw_llama7b_hbm_traffic.md: (46 335 018.56 x 1.999802 + 92 669 643.59 x 0.999987) KiB
+    # profiles/k_adamw_llama7b_hbm_traffic.md: (46 335 017.88 x 1.999802 + 92 668 588.22 x 0.999992) KiB
     "llama_7b": 189_776_597_297,
 }
 
