@@ -154,6 +154,42 @@ int main(int argc, char** argv) {
              14.0 * double(S) * n_host / t / 1e6);
     }
   }
+  // PROBE_ACCUM=<k> [PROBE_ZERO=1]: the gradient-accumulation variant on the same state: a second context
+  // with fp32 gradient chunks, k micro-batches accumulated per step, then norm and update
+  if (const char* ka = getenv("PROBE_ACCUM")) {
+    const int K = atoi(ka) > 0 ? atoi(ka) : 1;
+    pt_ctx* cx = nullptr;
+    CHECK_PT(nullptr, pt_ctx_create(&cx, PT_BF16, S, C, nullptr));
+    CHECK_PT(cx, pt_ctx_set_option(cx, "grad_fp32", 1));
+    if (getenv("PROBE_ZERO")) CHECK_PT(cx, pt_ctx_set_option(cx, "adamw_zero_grads", 1));
+    std::vector<float*> g32(C);
+    for (uint32_t c = 0; c < C; ++c) {
+      CHECK_HIP(hipMalloc((void**)&g32[c], 4 * S));
+      CHECK_HIP(hipMemset(g32[c], 0, 4 * S));
+    }
+    pt_pack_plan* pl = nullptr;
+    CHECK_PT(cx, pt_pack_plan_create(cx, segs.data(), C, &pl));
+    for (int s = 0; s < steps; ++s) {
+      CHECK_HIP(hipEventRecord(e[0], st));
+      for (int k = 0; k < K; ++k) CHECK_PT(cx, pt_chunk_accum_grads(cx, pl, g32.data(), k == 0, k == K - 1, st));
+      CHECK_HIP(hipEventRecord(e[1], st));
+      CHECK_PT(cx, pt_chunk_grad_sqnorm(cx, nullptr, 0, C, 1, st));
+      CHECK_HIP(hipEventRecord(e[2], st));
+      CHECK_PT(cx, pt_chunk_adamw_step(cx, &hpar, 0, C, (const void* const*)g32.data(), w.data(), m.data(), v.data(), p.data(), st));
+      CHECK_HIP(hipEventRecord(e[3], st));
+      CHECK_PT(cx, pt_step_end(cx, st));
+      CHECK_HIP(hipStreamSynchronize(st));
+      float ta, tu;
+      CHECK_HIP(hipEventElapsedTime(&ta, e[0], e[1]));
+      CHECK_HIP(hipEventElapsedTime(&tu, e[2], e[3]));
+      const double n = double(S) * C;
+      printf("accumulate step %d: %d micro-batches %.3f ms (%.0f GB/s)  adamw on fp32 gradients %.3f ms (%.0f GB/s)\n", s, K, ta,
+             (6.0 + 10.0 * (K - 1)) * n / ta / 1e6, tu, (getenv("PROBE_ZERO") ? 34.0 : 30.0) * n / tu / 1e6);
+    }
+    CHECK_PT(cx, pt_pack_plan_destroy(pl));
+    CHECK_PT(cx, pt_ctx_destroy(cx));
+    for (uint32_t c = 0; c < C; ++c) CHECK_HIP(hipFree(g32[c]));
+  }
   // PROBE_PACK_TILES="8192,16384,...": times pack with plans of each tile size, same process
   if (const char* tl = getenv("PROBE_PACK_TILES")) {
     for (const char* q = tl; *q;) {
