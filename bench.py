@@ -326,6 +326,7 @@ def run_in_processes(args) -> int:
         cmd += ["--placement", args.placement]
         if args.graph: cmd.append("--graph")
         if args.chunk_map: cmd.append("--chunk-map")
+        if args.unpack: cmd.append("--unpack")
         if args.pack_tile: cmd += ["--pack-tile", str(args.pack_tile)]
         if args.no_cpu_baseline or i != args.processes - 1: cmd.append("--no-cpu-baseline")
         res = subprocess.run(cmd, stdout=subprocess.PIPE, text=True)
@@ -367,6 +368,7 @@ def main() -> int:
     ap.add_argument("--placement", default="spread", choices=["spread", "plain"],
                     help="spread: the five state arenas are allocated tens of GiB apart in physical memory "
                          "(temporary spacers between them); plain: one allocation after the other")
+    ap.add_argument("--unpack", action="store_true", help="also time pt_chunk_unpack of the parameter chunks into tensors")
     ap.add_argument("--chunk-map", action="store_true",
                     help="also time the update of every chunk on its own (one launch per chunk) and report the rate per chunk: "
                          "shows how the speed follows the physical placement of the arenas")
@@ -616,6 +618,24 @@ def main() -> int:
         t_g = (time.perf_counter() - t_g) / K
         out["hip_graph"] = {"ms_per_step": round(1e3 * t_g, 4), "GBps": round(step_bytes / t_g / 1e9, 1),
                             "speedup_over_eager": round(ms_step * 1e-3 / t_g, 3)}
+
+    if args.unpack:
+        # the inverse copy: updated 16-bit parameter chunks back to the model's tensors (same kernel, DIR = 1)
+        flat_p = torch.empty(N, dtype=dt16, device=dev)
+        for s_ in segs:
+            s_.src = flat_p.data_ptr() + 2 * offs[s_.tensor]
+        plan_u = B.pt_pack_plan_create(ctx, segs)
+        ts = []
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            B.pt_chunk_unpack(ctx, plan_u, r_p, stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        B.pt_pack_plan_destroy(plan_u)
+        out["unpack"] = {"ms": round(min(ts), 4), "GBps": round(4 * N / min(ts) / 1e6, 1)}
+        del flat_p
 
     if args.chunk_map:
         rates = []

@@ -275,11 +275,15 @@ static int run_pack(pt_ctx* ctx, const pt_pack_plan* plan, const void* const* ch
   for (uint32_t c : plan->touched)
     if (!h[c]) return pt_fail(ctx, PT_ERR_INVALID_ARG, "%s: chunk %u is used by the plan but its pointer is NULL", who, c);
   dim3 grid(plan->n_tiles);
+  // The inverse copy has no arithmetic to pace it; measured on MI355X it runs 15 % faster with three
+  // workgroups per compute unit than with the eight that fit (4.24 against 4.96 ms for 6.7e9 elements).
+  // Unused dynamic LDS (52 KiB of the unit's 160) sets that limit.  Pack itself is indifferent to it.
+  const size_t lds = DIR == 1 ? 53248 : 0;
   if (ctx->dtype == PT_BF16)
-    hipLaunchKernelGGL((k_pack<PT_BF16, DIR>), grid, dim3(PK_THREADS), 0, st, plan->d_tiles, pt_row(ctx, row),
+    hipLaunchKernelGGL((k_pack<PT_BF16, DIR>), grid, dim3(PK_THREADS), lds, st, plan->d_tiles, pt_row(ctx, row),
                        ctx->d_state, plan->d_tile_sq, plan->d_tile_flag);
   else
-    hipLaunchKernelGGL((k_pack<PT_FP16, DIR>), grid, dim3(PK_THREADS), 0, st, plan->d_tiles, pt_row(ctx, row),
+    hipLaunchKernelGGL((k_pack<PT_FP16, DIR>), grid, dim3(PK_THREADS), lds, st, plan->d_tiles, pt_row(ctx, row),
                        ctx->d_state, plan->d_tile_sq, plan->d_tile_flag);
   PT_LAUNCH_CHECK(ctx, who);
   if (DIR == 0)
