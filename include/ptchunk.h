@@ -210,7 +210,7 @@ int pt_chunk_pack_grads(pt_ctx* ctx, const pt_pack_plan* plan, void* const* grad
 /* Gradient accumulation over micro-batches (a variant; needs option "grad_fp32").  For every
  * element of every segment of the plan: acc = decode(src word) if `overwrite` (first
  * micro-batch), else acc = acc + decode(src word), one binary32 addition.  acc_chunks: host
- * array of ctx.n_chunks device pointers to chunk_elems floats each (256-byte aligned; entries
+ * array of ctx.n_chunks device pointers to chunk_elems floats each (16-byte aligned; entries
  * of chunks the plan does not touch may be NULL); elements no segment covers are not written.
  * take_norm != 0 (the last micro-batch): as pt_chunk_pack_grads, leaves per chunk the fp64 sum of
  * (acc/loss_scale)^2 and the non-finite flag of the ACCUMULATED values in the context, for
