@@ -17,7 +17,7 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int AC_THREADS = 256;
+constexpr int AC_THREADS = PT_REDUCE_THREADS;
 
 template <int DT>
 __device__ __forceinline__ float word_to_f32(uint32_t w16) {
@@ -130,23 +130,11 @@ k_accum(const PtTile* __restrict__ tiles, const uint64_t* __restrict__ chunk_row
   }
 
   if (NORM) {
-    // fixed-order block reduction: 64-lane shuffle tree, then the four waves in order
-    __shared__ double s_sum[AC_THREADS / 64];
-    __shared__ uint32_t s_flag[AC_THREADS / 64];
     double acc = a0 + a1;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
-    const uint32_t f = __any(flag != 0) ? 1u : 0u;
-    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
-    if (lane == 0) { s_sum[wid] = acc; s_flag[wid] = f; }
-    __syncthreads();
+    pt_block_sum(acc, flag);
     if (threadIdx.x == 0) {
-      double tsum = s_sum[0];
-      uint32_t g = s_flag[0];
-#pragma unroll
-      for (int k = 1; k < AC_THREADS / 64; ++k) { tsum += s_sum[k]; g |= s_flag[k]; }
-      tile_sq[tidx] = tsum;
-      tile_flag[tidx] = g;
+      tile_sq[tidx] = acc;
+      tile_flag[tidx] = flag;
     }
   }
 }

@@ -163,6 +163,33 @@ inline int pt_guarded(pt_ctx* ctx, const char* who, F&& body) noexcept {
                      hipGetErrorString(e__));                                          \
   } while (0)
 
+// ---- fixed-order block reduction (device) --------------------------------------------
+// Sum of `acc` and OR of `flag` over a workgroup of 256 threads, in a fixed order: a 64-lane
+// shuffle tree per wave, then the four waves one after the other through LDS.  No atomics, so a
+// result does not depend on timing.  The result is valid in thread 0 only.  Every kernel that
+// leaves a partial sum of squares (pack, accumulate, the standalone norm, the per-chunk sums)
+// reduces through this one function, so their partials are interchangeable bit for bit.
+constexpr int PT_REDUCE_THREADS = 256;
+
+__device__ __forceinline__ void pt_block_sum(double& acc, uint32_t& flag) {
+  __shared__ double s_sum[PT_REDUCE_THREADS / 64];
+  __shared__ uint32_t s_flag[PT_REDUCE_THREADS / 64];
+  double w = acc;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) w += __shfl_down(w, off, 64);
+  const uint32_t f = __any(flag != 0) ? 1u : 0u;
+  const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
+  if (lane == 0) { s_sum[wid] = w; s_flag[wid] = f; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = s_sum[0];
+    uint32_t g = s_flag[0];
+#pragma unroll
+    for (int i = 1; i < PT_REDUCE_THREADS / 64; ++i) { t += s_sum[i]; g |= s_flag[i]; }
+    acc = t; flag = g;
+  }
+}
+
 // ---- helpers implemented in pt_ctx.hip ---------------------------------------------
 // Makes rows[r][first .. first+n) of the device pointer table equal to ptrs[0..n);
 // re-uploads (after synchronising `stream`) only when something changed.

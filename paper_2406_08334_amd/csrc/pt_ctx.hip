@@ -4,8 +4,6 @@
 
 #include <algorithm>
 
-#include <cstdlib>
-
 static thread_local std::string g_noctx_error;
 
 int pt_fail(pt_ctx* ctx, int status, const char* fmt, ...) noexcept {
@@ -525,10 +523,6 @@ extern "C" int pt_calib_copy(void* dst, const void* src, uint64_t bytes, void* s
   uint64_t n_vec = bytes / 16;
   uint64_t blocks = (n_vec + 1023) / 1024;
   if (blocks > 256 * 32) blocks = 256 * 32;
-  if (const char* e = getenv("PTCHUNK_COPY_BLOCKS")) {        // calibration experiments only
-    uint64_t b = strtoull(e, nullptr, 10);
-    if (b > 0 && b <= (1u << 24)) blocks = b;
-  }
   hipLaunchKernelGGL(k_calib_copy, dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream,
                      (u32x4_t*)dst, (const u32x4_t*)src, n_vec);
   if (hipGetLastError() != hipSuccess) return pt_fail(nullptr, PT_ERR_HIP, "pt_calib_copy: launch failed");

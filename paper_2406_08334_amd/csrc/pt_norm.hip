@@ -15,7 +15,7 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int NB_THREADS = 256;
+constexpr int NB_THREADS = PT_REDUCE_THREADS;
 
 template <int DT>
 __device__ __forceinline__ double word_to_f64(uint32_t w16) {
@@ -46,30 +46,6 @@ __device__ __forceinline__ void accum_vec(const u32x4& q, double inv_scale, doub
     a0 = fma(x0, x0, a0);
     a1 = fma(x1, x1, a1);
     flag |= pair_nonfinite<DT>(w[k]);
-  }
-}
-
-__device__ __forceinline__ double wave_sum(double x) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) x += __shfl_down(x, off, 64);
-  return x;  // valid in lane 0
-}
-
-// Block-wide sum in a fixed order; result valid in thread 0.
-__device__ __forceinline__ void block_sum(double& acc, uint32_t& flag) {
-  __shared__ double s_sum[NB_THREADS / 64];
-  __shared__ uint32_t s_flag[NB_THREADS / 64];
-  double w = wave_sum(acc);
-  uint32_t f = __any(flag != 0) ? 1u : 0u;
-  int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
-  if (lane == 0) { s_sum[wid] = w; s_flag[wid] = f; }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    double t = s_sum[0];
-    uint32_t g = s_flag[0];
-#pragma unroll
-    for (int i = 1; i < NB_THREADS / 64; ++i) { t += s_sum[i]; g |= s_flag[i]; }
-    acc = t; flag = g;
   }
 }
 
@@ -105,7 +81,7 @@ k_sqnorm(const uint64_t* __restrict__ grad_row, uint32_t first, uint64_t S,
     accum_vec<DT>(q, inv_scale, a0, a1, flag);
   }
   double acc = a0 + a1;
-  block_sum(acc, flag);
+  pt_block_sum(acc, flag);
   if (threadIdx.x == 0) {
     size_t slot = size_t(i) * gridDim.x + b;
     part[slot] = acc;
@@ -158,7 +134,7 @@ k_sqnorm_f32(const uint64_t* __restrict__ grad_row, uint32_t first, uint64_t S,
     accum_vec_f32(q, inv_scale, a0, a1, flag);
   }
   double acc = a0 + a1;
-  block_sum(acc, flag);
+  pt_block_sum(acc, flag);
   if (threadIdx.x == 0) {
     size_t slot = size_t(i) * gridDim.x + b;
     part[slot] = acc;
@@ -181,7 +157,7 @@ k_chunk_reduce(const double* __restrict__ part, const uint32_t* __restrict__ fla
   double acc = 0.0;
   uint32_t f = 0;
   for (uint32_t k = lo + threadIdx.x; k < hi; k += NB_THREADS) { acc += part[k]; f |= flag[k]; }
-  block_sum(acc, f);
+  pt_block_sum(acc, f);
   if (threadIdx.x == 0) { chunk_sq[c] = acc; chunk_flag[c] = f; }
 }
 

@@ -19,7 +19,7 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int PK_THREADS = 256;
+constexpr int PK_THREADS = PT_REDUCE_THREADS;
 
 template <int DT>
 __device__ __forceinline__ double word_sq(uint32_t w16, double inv_scale) {
@@ -134,23 +134,11 @@ k_pack(const PtTile* __restrict__ tiles, const uint64_t* __restrict__ chunk_row,
   }
 
   if (DIR == 0) {
-    // fixed-order block reduction: 64-lane shuffle tree, then the four waves in order
-    __shared__ double s_sum[PK_THREADS / 64];
-    __shared__ uint32_t s_flag[PK_THREADS / 64];
     double acc = a0 + a1;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
-    uint32_t f = __any(flag != 0) ? 1u : 0u;
-    const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
-    if (lane == 0) { s_sum[wid] = acc; s_flag[wid] = f; }
-    __syncthreads();
+    pt_block_sum(acc, flag);
     if (threadIdx.x == 0) {
-      double tsum = s_sum[0];
-      uint32_t g = s_flag[0];
-#pragma unroll
-      for (int i = 1; i < PK_THREADS / 64; ++i) { tsum += s_sum[i]; g |= s_flag[i]; }
-      tile_sq[blockIdx.x] = tsum;
-      tile_flag[blockIdx.x] = g;
+      tile_sq[blockIdx.x] = acc;
+      tile_flag[blockIdx.x] = flag;
     }
   }
 }

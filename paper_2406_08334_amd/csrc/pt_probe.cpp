@@ -66,23 +66,16 @@ int main(int argc, char** argv) {
     memcpy(&hw[i], &b, 4);
   }
 
-  // PROBE_SKEW=<bytes> (multiple of 16): array k of a chunk starts k*skew bytes into its
-  // allocation, to see how the relative placement of the five arrays matters
-  const size_t skew = getenv("PROBE_SKEW") ? strtoull(getenv("PROBE_SKEW"), nullptr, 10) & ~size_t(15) : 0;
-  const size_t extra = 6 * skew;
   std::vector<void*> src(C), g(C), p(C);
   std::vector<float*> w(C), m(C), v(C);
   for (uint32_t c = 0; c < C; ++c) {
     char* q;
-    // PROBE_SRC_SHIFT=<elements>: gradient tensors start that many elements into their allocation
-    // (1..7 makes source and chunk incongruent modulo 16 bytes)
-    const size_t src_shift = getenv("PROBE_SRC_SHIFT") ? 2 * (strtoull(getenv("PROBE_SRC_SHIFT"), nullptr, 10) & 7) : 0;
-    CHECK_HIP(hipMalloc((void**)&q, 2 * S + extra + 16)); src[c] = q + src_shift;
-    CHECK_HIP(hipMalloc((void**)&q, 2 * S + extra)); g[c] = q + 1 * skew;
-    CHECK_HIP(hipMalloc((void**)&q, 2 * S + extra)); p[c] = q + 2 * skew;
-    CHECK_HIP(hipMalloc((void**)&q, 4 * S + extra)); w[c] = (float*)(q + 3 * skew);
-    CHECK_HIP(hipMalloc((void**)&q, 4 * S + extra)); m[c] = (float*)(q + 4 * skew);
-    CHECK_HIP(hipMalloc((void**)&q, 4 * S + extra)); v[c] = (float*)(q + 5 * skew);
+    CHECK_HIP(hipMalloc((void**)&q, 2 * S)); src[c] = q;
+    CHECK_HIP(hipMalloc((void**)&q, 2 * S)); g[c] = q;
+    CHECK_HIP(hipMalloc((void**)&q, 2 * S)); p[c] = q;
+    CHECK_HIP(hipMalloc((void**)&q, 4 * S)); w[c] = (float*)q;
+    CHECK_HIP(hipMalloc((void**)&q, 4 * S)); m[c] = (float*)q;
+    CHECK_HIP(hipMalloc((void**)&q, 4 * S)); v[c] = (float*)q;
     CHECK_HIP(hipMemcpy(src[c], hg.data(), 2 * S, hipMemcpyHostToDevice));
     CHECK_HIP(hipMemcpy(p[c], hp.data(), 2 * S, hipMemcpyHostToDevice));
     CHECK_HIP(hipMemcpy(w[c], hw.data(), 4 * S, hipMemcpyHostToDevice));
@@ -189,61 +182,6 @@ int main(int argc, char** argv) {
     CHECK_PT(cx, pt_pack_plan_destroy(pl));
     CHECK_PT(cx, pt_ctx_destroy(cx));
     for (uint32_t c = 0; c < C; ++c) CHECK_HIP(hipFree(g32[c]));
-  }
-  // PROBE_PACK_TILES="8192,16384,...": times pack with plans of each tile size, same process
-  if (const char* tl = getenv("PROBE_PACK_TILES")) {
-    for (const char* q = tl; *q;) {
-      char* end; long te = strtol(q, &end, 10); q = (*end == ',') ? end + 1 : end;
-      CHECK_PT(ctx, pt_ctx_set_option(ctx, "pack_tile_elems", te));
-      pt_pack_plan* pl = nullptr;
-      CHECK_PT(ctx, pt_pack_plan_create(ctx, segs.data(), C, &pl));
-      float best = 1e30f;
-      for (int k = 0; k < 4; ++k) {
-        CHECK_HIP(hipEventRecord(e[0], st));
-        CHECK_PT(ctx, pt_chunk_pack_grads(ctx, pl, g.data(), st));
-        CHECK_HIP(hipEventRecord(e[1], st));
-        CHECK_HIP(hipStreamSynchronize(st));
-        float t; CHECK_HIP(hipEventElapsedTime(&t, e[0], e[1]));
-        if (t < best) best = t;
-      }
-      printf("pack tile %8ld: best of 4 %.3f ms (%.0f GB/s)\n", te, best, 4.0 * double(S) * C / best / 1e6);
-      CHECK_PT(ctx, pt_pack_plan_destroy(pl));
-      if (end == q && *q) break;
-    }
-  }
-  // PROBE_GRIDS="4096,16384,..." [PROBE_UNROLLS="4,8"] [PROBE_NT="1,0"]: times the update alone for
-  // every combination, in this one process on these allocations (placement differs run to run)
-  if (const char* gl = getenv("PROBE_GRIDS")) {
-    auto parse = [](const char* q, std::vector<long>& out) {
-      while (q && *q) { char* end; out.push_back(strtol(q, &end, 10)); q = (*end == ',') ? end + 1 : end; if (end == q && *q) break; }
-    };
-    std::vector<long> grids, unrolls, nts;
-    parse(gl, grids);
-    parse(getenv("PROBE_UNROLLS"), unrolls);
-    parse(getenv("PROBE_NT"), nts);
-    if (unrolls.empty()) unrolls.push_back(8);
-    if (nts.empty()) nts.push_back(1);
-    for (long nt : nts)
-      for (long un : unrolls)
-        for (long gsz : grids) {
-          CHECK_PT(ctx, pt_ctx_set_option(ctx, "adamw_nt", nt));
-          CHECK_PT(ctx, pt_ctx_set_option(ctx, "adamw_unroll", un));
-          CHECK_PT(ctx, pt_ctx_set_option(ctx, "adamw_grid", gsz));
-          float best = 1e30f;
-          for (int k = 0; k < 3; ++k) {
-            CHECK_PT(ctx, pt_step_override(ctx, 0.0121f, 0, st));
-            CHECK_HIP(hipEventRecord(e[0], st));
-            CHECK_PT(ctx, pt_chunk_adamw_step(ctx, &hpar, 0, C, g.data(), w.data(), m.data(), v.data(), p.data(), st));
-            CHECK_HIP(hipEventRecord(e[1], st));
-            CHECK_PT(ctx, pt_step_end(ctx, st));
-            CHECK_HIP(hipStreamSynchronize(st));
-            float t;
-            CHECK_HIP(hipEventElapsedTime(&t, e[0], e[1]));
-            if (t < best) best = t;
-          }
-          printf("adamw nt %ld unroll %ld grid %7ld: best of 3 %.3f ms (%.0f GB/s)\n", nt, un, gsz, best,
-                 28.0 * double(S) * C / best / 1e6);
-        }
   }
   // standalone norm over all chunks (reads 2 bytes per element)
   {
