@@ -49,21 +49,17 @@ __device__ __forceinline__ void accum_vec(const u32x4& q, double inv_scale, doub
   }
 }
 
-// grid = (norm_blocks, n_chunks).  Block (b, i) reduces elements
-// [b*PT_NORM_BLOCK_ELEMS, min(S, (b+1)*PT_NORM_BLOCK_ELEMS)) of chunk first+i.
+// One block's share of a chunk: the fp64 sum of (g/scale)^2 and the non-finite flag over elements
+// [b*PT_NORM_BLOCK_ELEMS, min(S, (b+1)*PT_NORM_BLOCK_ELEMS)) of the chunk at `base`; valid in thread 0.
 template <int DT>
-__global__ void __launch_bounds__(NB_THREADS)
-k_sqnorm(const uint64_t* __restrict__ grad_row, uint32_t first, uint64_t S,
-         const PtDevState* __restrict__ st, double* __restrict__ part, uint32_t* __restrict__ flagout) {
-  const uint32_t b = blockIdx.x, i = blockIdx.y;
-  const PT_GLOBAL u32x4* base = (const PT_GLOBAL u32x4*)(grad_row[first + i]);   // global_* loads
+__device__ __forceinline__ void sqnorm_block(const PT_GLOBAL u32x4* base, uint64_t S, uint32_t b, double inv_scale,
+                                             double& acc, uint32_t& flag) {
   const uint64_t vec_total = S / 8;
   const uint64_t v0 = uint64_t(b) * (PT_NORM_BLOCK_ELEMS / 8);
   uint64_t v1 = v0 + PT_NORM_BLOCK_ELEMS / 8;
   if (v1 > vec_total) v1 = vec_total;
-  const double inv_scale = 1.0 / st->loss_scale;
   double a0 = 0.0, a1 = 0.0;
-  uint32_t flag = 0;
+  flag = 0;
   uint64_t v = v0 + threadIdx.x;
   // four independent 16-byte loads in flight per lane
   for (; v + 3 * NB_THREADS < v1; v += 4 * NB_THREADS) {
@@ -80,8 +76,21 @@ k_sqnorm(const uint64_t* __restrict__ grad_row, uint32_t first, uint64_t S,
     u32x4 q = __builtin_nontemporal_load(base + v);
     accum_vec<DT>(q, inv_scale, a0, a1, flag);
   }
-  double acc = a0 + a1;
+  acc = a0 + a1;
   pt_block_sum(acc, flag);
+}
+
+// grid = (norm_blocks, n_chunks).  Block (b, i) reduces its share of chunk first+i, whose base
+// pointer comes from the context's pointer table.
+template <int DT>
+__global__ void __launch_bounds__(NB_THREADS)
+k_sqnorm(const uint64_t* __restrict__ grad_row, uint32_t first, uint64_t S,
+         const PtDevState* __restrict__ st, double* __restrict__ part, uint32_t* __restrict__ flagout) {
+  const uint32_t b = blockIdx.x, i = blockIdx.y;
+  const PT_GLOBAL u32x4* base = (const PT_GLOBAL u32x4*)(grad_row[first + i]);   // global_* loads
+  double acc;
+  uint32_t flag;
+  sqnorm_block<DT>(base, S, b, 1.0 / st->loss_scale, acc, flag);
   if (threadIdx.x == 0) {
     size_t slot = size_t(i) * gridDim.x + b;
     part[slot] = acc;
