@@ -1,102 +1,110 @@
-"""CPU oracle of the paper-faithful chunk layout and chunk-size search.
+"""CPU oracle of the paper's own chunk layout and chunk-size search.
 
 TEST INFRASTRUCTURE ONLY (same rules as oracle.cpp: never imported by the product).
-Plain Python loops, written from the paper's description:
+Plain Python, written from the paper's description (Appendix B.1, "Chunk Organization and
+Size Search"):
 
-  * parameters are laid out in the order given (execution order; a parameter shared
-    between layers appears once, at its first occurrence) - Appendix B.1, "Chunk
-    Organization and Size Search";
-  * parameters of one transformer block are grouped into one chunk - same passage;
-  * a parameter is never split between chunks, so chunks carry unused space ("memory
-    waste") - same passage, which chooses the chunk size by simulating that waste over
-    candidate sizes and taking the minimum.
+  * parameters are laid out in the order given (execution order; a parameter shared between
+    layers appears once, at its first occurrence);
+  * the parameters of one transformer block go into one chunk;
+  * a parameter is never split between chunks, so chunks carry unused space, and the chunk
+    size is chosen by simulating that waste over a grid of candidate sizes and taking the
+    size that wastes least.
 
-The paper gives neither the candidate grid nor a tie rule.  Reading taken here: the
-candidates are S_min, S_min + step, ... <= S_min + span with S_min = the largest
-parameter rounded up to `step`; ties go to the smaller size.  With span = 2^25 and
-step = 2^20 elements this reproduces both chunk counts the paper prints (Table 4:
-12 chunks for the 32-block GPT-2 1B, 49 for the 48-block GPT-2 10B).
+How this file states it.  The tensors stand in a row; a chunk boundary is a CUT between two
+neighbouring tensors.  A cut is FORBIDDEN between two tensors of the same transformer block
+when that block, laid out on its own from the start of a chunk, fits a chunk of S elements
+(then the block must stay whole); every other cut is allowed.  Chunks are filled from the
+left: a chunk that starts at tensor p ends at the LAST allowed cut q for which the tensors
+p .. q-1, laid one after the other, still fit S.  If not even the first allowed cut after p
+fits, some single tensor is larger than S and S is infeasible.  Inside a chunk every tensor
+starts at the next multiple of ALIGN = 8 elements (16 bytes, the vector width of the copy
+kernels); a tensor of size 0 takes no room and has no place.
 
-Placement rule for a given chunk size S (elements):
-  - walk the tensors in order; maximal runs of consecutive tensors with the same group
-    id (a transformer block) form a group, tensors with group id None stand alone;
-  - every tensor starts at a multiple of ALIGN = 8 elements inside its chunk (16 bytes:
-    the vector width of the copy kernels);
-  - a group that fits into an empty chunk is kept together: if it does not fit into the
-    rest of the current chunk, the chunk is closed and the group opens the next one;
-  - a group larger than a chunk is placed tensor by tensor under the same rule;
-  - a tensor larger than S makes S infeasible.
+Readings where the paper is silent: the candidate grid is S_min, S_min + step, ... up to
+S_min + span, with S_min = max(largest tensor, min_chunk) rounded up to a multiple of `step`;
+among sizes of equal waste the smallest wins.  Pins: tests/test_oracle_layout.py (hand-worked
+placements, structural invariants on random inputs, brute force over every candidate, and
+the chunk counts the paper prints in its Table 4, which some - not all - grids reproduce).
 """
 from __future__ import annotations
 
 ALIGN = 8
 
 
-def _up(x: int, a: int) -> int:
-    return -(-x // a) * a
+def end_offset(sizes, first: int, last: int) -> int:
+    """Elements a chunk needs to hold tensors first .. last-1 from its start, each at the next
+    multiple of ALIGN (empty tensors skipped)."""
+    end = 0
+    for t in range(first, last):
+        if sizes[t]:
+            end = (end + ALIGN - 1) // ALIGN * ALIGN + sizes[t]
+    return end
 
 
-def _groups(sizes, group_ids):
-    """maximal runs of equal non-None group ids -> list of lists of tensor indices"""
-    runs, i, n = [], 0, len(sizes)
-    while i < n:
-        j = i + 1
-        if group_ids[i] is not None:
-            while j < n and group_ids[j] == group_ids[i]:
-                j += 1
-        runs.append(list(range(i, j)))
-        i = j
-    return runs
-
-
-def _span(sizes, idxs, start: int) -> int:
-    """end offset after placing tensors idxs one after the other from offset `start`"""
-    off = start
-    for t in idxs:
-        if sizes[t] == 0:
+def allowed_cuts(sizes, group_ids, S: int):
+    """cut[k] is True when a chunk boundary may fall between tensor k-1 and tensor k (0 < k < n)."""
+    n = len(sizes)
+    cut = [True] * (n + 1)
+    k = 0
+    while k < n:
+        if group_ids[k] is None:
+            k += 1
             continue
-        off = _up(off, ALIGN) + sizes[t]
-    return off
+        stop = k                       # the block: tensors k .. stop-1 carry the same id in a row
+        while stop < n and group_ids[stop] == group_ids[k]:
+            stop += 1
+        if end_offset(sizes, k, stop) <= S:
+            for inner in range(k + 1, stop):
+                cut[inner] = False     # the block fits a chunk: it stays whole
+        k = stop
+    return cut
 
 
 def layout_grouped(sizes, group_ids, S: int):
-    """-> (placements, n_chunks, waste) or None if S is infeasible.
-    placements[t] = (chunk, offset) or None for an empty tensor; waste = n_chunks*S - sum(sizes)."""
+    """-> (placements, n_chunks, waste), or None when a tensor is larger than S.
+    placements[t] = (chunk, offset), None for an empty tensor; waste = n_chunks * S - sum(sizes)."""
     assert S > 0 and S % ALIGN == 0
-    place = [None] * len(sizes)
-    chunk, off, used_any = 0, 0, False
-    for run in _groups(sizes, group_ids):
-        pieces = [run] if _span(sizes, run, 0) <= S else [[t] for t in run]
-        for piece in pieces:
-            if all(sizes[t] == 0 for t in piece):
-                continue
-            if _span(sizes, piece, 0) > S:
-                return None
-            if _span(sizes, piece, off) > S:
-                chunk, off = chunk + 1, 0
-            for t in piece:
-                if sizes[t] == 0:
-                    continue
-                off = _up(off, ALIGN)
+    n = len(sizes)
+    cut = allowed_cuts(sizes, group_ids, S)
+    place = [None] * n
+    chunk = 0
+    p = 0
+    while p < n and sizes[p] == 0:     # leading empty tensors belong to no chunk
+        p += 1
+    while p < n:
+        best = None
+        for q in range(p + 1, n + 1):
+            if cut[q] and end_offset(sizes, p, q) <= S:
+                best = q               # keep the last allowed cut that still fits
+        if best is None:
+            return None
+        q = best
+        while q < n and sizes[q] == 0:  # empty tensors after the cut take no room anywhere
+            q += 1
+        off = 0
+        for t in range(p, best):
+            if sizes[t]:
+                off = (off + ALIGN - 1) // ALIGN * ALIGN
                 place[t] = (chunk, off)
                 off += sizes[t]
-                used_any = True
-    n_chunks = chunk + 1 if used_any else 0
-    return place, n_chunks, n_chunks * S - sum(sizes)
+        chunk += 1
+        p = q
+    return place, chunk, chunk * S - sum(sizes)
 
 
 def chunk_size_search(sizes, group_ids, min_chunk: int, span: int, step: int):
-    """-> (best S, n_chunks, waste): minimum waste over the candidate grid, ties to the smaller S."""
-    assert step % ALIGN == 0 and step > 0
-    biggest = max([s for s in sizes] + [1])
-    s_min = _up(max(biggest, min_chunk), step)
-    best = None
-    S = s_min
-    while S <= s_min + span:
+    """-> (S, n_chunks, waste) of least waste over the grid, the smaller S on equal waste."""
+    assert step > 0 and step % ALIGN == 0
+    floor = max(max(list(sizes) + [1]), min_chunk)
+    s_min = (floor + step - 1) // step * step
+    outcomes = []
+    for k in range(span // step + 1):
+        S = s_min + k * step
         r = layout_grouped(sizes, group_ids, S)
         if r is not None:
-            _, n_chunks, waste = r
-            if best is None or waste < best[2]:
-                best = (S, n_chunks, waste)
-        S += step
-    return best
+            outcomes.append((r[2], S, r[1]))           # (waste, S, n_chunks): min() orders by waste, then S
+    if not outcomes:
+        return None
+    waste, S, n_chunks = min(outcomes)
+    return S, n_chunks, waste

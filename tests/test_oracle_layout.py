@@ -1,7 +1,11 @@
-"""Pins for the oracle's paper-faithful layout (no tensor split, transformer blocks kept
+"""Pins for the oracle's layout after the paper (no tensor split, transformer blocks kept
 together, chunk size by minimum-waste search; paper, Appendix B.1 "Chunk Organization and
-Size Search"): the chunk counts the paper prints in Table 4, structural invariants, and a
-brute-force search over every candidate size on small inputs."""
+Size Search"): placements worked out by hand for the LLaMA-7B table and a GPT-2 block,
+structural invariants on random inputs, and a brute-force search over every candidate size
+on small inputs.  The chunk counts the paper prints in Table 4 are a consistency check, not
+a pin: 49 chunks for the 48-block GPT2-10B follows from any grid (one block per chunk plus
+the embeddings), and 12 chunks for the 32-block GPT2-1B - whose hidden size the paper does
+not print - comes out for hidden sizes 1280 to 1792 under several (span, step) grids."""
 import os
 import random
 
@@ -15,7 +19,7 @@ MODELS = {"gpt2_1b": lambda: shapes.gpt2(1600, 32, 6400), "gpt2_10b": lambda: sh
 SPAN, STEP = 1 << 25, 1 << 20
 
 
-def test_search_reproduces_the_papers_chunk_counts():
+def test_search_is_consistent_with_the_papers_chunk_counts():
     rows = [l.split() for l in open(GOLDEN) if l.strip() and not l.startswith("#")]
     assert len(rows) == 2
     for name, n_block, n_chunk in rows:
@@ -51,8 +55,28 @@ def check_invariants(sizes, gids, S, place, n_chunks):
         if g is not None and sizes[t]:
             by_gid.setdefault((g, _run_id(gids, t)), []).append(t)
     for ts in by_gid.values():
-        if L._span(sizes, ts, 0) <= S:
+        need = 0                                              # room the block takes on its own, 8-aligned starts
+        for t in ts:
+            need = -(-need // 8) * 8 + sizes[t]
+        if need <= S:
             assert len({place[t][0] for t in ts}) == 1
+    # left-filled: the first tensor (or whole block) of a chunk would not have fitted behind the chunk before it
+    first_of = {c: min(v)[2] for c, v in spans.items()}
+    for c in range(1, n_chunks):
+        t0 = first_of[c]
+        block = [t0]
+        if gids[t0] is not None:
+            rid = _run_id(gids, t0)
+            block = [t for t in range(len(sizes)) if gids[t] == gids[t0] and _run_id(gids, t) == rid and sizes[t]]
+            alone = 0
+            for t in block:
+                alone = -(-alone // 8) * 8 + sizes[t]
+            if alone > S:                                     # a block too big for a chunk goes tensor by tensor
+                block = [t0]
+        end = max(e for _, e, _ in spans[c - 1])
+        for t in block:
+            end = -(-end // 8) * 8 + sizes[t]
+        assert end > S, (c, t0)
 
 
 def _run_id(gids, t):
@@ -95,6 +119,51 @@ def test_worked_small_example():
     place, n_chunks, _ = L.layout_grouped([20, 20, 20], [7, 7, 7], 32)
     assert place == [(0, 0), (1, 0), (2, 0)] and n_chunks == 3
     assert L.layout_grouped([40], [None], 32) is None
+
+
+def test_llama7b_placements_worked_by_hand():
+    """LLaMA-7B shape, S = 194 * 2^20 = 203,423,744.  By hand: the embedding (32000 * 4096 = 131,072,000)
+    opens chunk 0; a block is 4 * 4096^2 + 3 * 4096 * 11008 + 2 * 4096 = 202,383,360 elements, more than the
+    72,351,744 left in chunk 0, so block i fills chunk 1 + i and leaves 1,040,384; the final norm gain (4096)
+    fits behind block 31 in chunk 32; the head (131,072,000) does not and opens chunk 33: 34 chunks,
+    waste 34 * 203,423,744 - 6,738,415,616 = 177,991,680."""
+    table = shapes.llama(4096, 11008, 32)
+    sizes, gids = [n for _, n in table], shapes.block_ids(table)
+    S = 194 << 20
+    place, n_chunks, waste = L.layout_grouped(sizes, gids, S)
+    assert n_chunks == 34 and waste == 177_991_680
+    assert place[0] == (0, 0)
+    inside = [0, 16_777_216, 33_554_432, 50_331_648, 67_108_864, 112_197_632, 157_286_400, 202_375_168, 202_379_264]
+    for i in range(32):
+        assert place[1 + 9 * i: 10 + 9 * i] == [(1 + i, off) for off in inside], i
+    assert place[289] == (32, 202_383_360)        # norm.weight behind the last block
+    assert place[290] == (33, 0)                  # lm_head.weight
+    # one step smaller (193 * 2^20 = 202,375,168 < a block): blocks no longer fit a chunk and go tensor by tensor
+    place2, n2, _ = L.layout_grouped(sizes, gids, 193 << 20)
+    assert place2[1:10] == [(0, 131_072_000), (0, 147_849_216), (0, 164_626_432), (0, 181_403_648),
+                            (1, 0), (1, 45_088_768), (1, 90_177_536), (1, 135_266_304), (1, 135_270_400)]
+
+
+def test_gpt2_block_placements_worked_by_hand():
+    """GPT-2 block, hidden 768 (7,087,872 elements: 768, 768, 1,769,472, 2304, 589,824, 768, 768, 768,
+    2,359,296, 3072, 2,359,296, 768), preceded and followed by a lone tensor of 1000 elements."""
+    blk = [n for _, n in shapes.gpt2_block(768)]
+    sizes, gids = [1000] + blk + [1000], [None] + [0] * 12 + [None]
+    # S = 7,089,000: the lone tensor takes [0, 1000); the block (7,087,872) would end at 7,088,872 <= S: same chunk
+    place, n_chunks, waste = L.layout_grouped(sizes, gids, 7_089_000)
+    starts = [1000, 1768, 2536, 1_772_008, 1_774_312, 2_364_136, 2_364_904, 2_365_672, 2_366_440, 4_725_736,
+              4_728_808, 7_088_104]
+    assert place[0] == (0, 0) and place[1:13] == [(0, o) for o in starts]
+    assert place[13] == (1, 0) and n_chunks == 2       # 7,088,872 + 1000 > S
+    assert waste == 2 * 7_089_000 - sum(sizes)
+    # S = 7,088,000: the block fits an empty chunk (7,087,872) but not behind the lone tensor: it opens chunk 1
+    place, n_chunks, _ = L.layout_grouped(sizes, gids, 7_088_000)
+    assert place[0] == (0, 0) and place[1] == (1, 0) and place[12] == (1, 7_087_104) and place[13] == (2, 0)
+    assert n_chunks == 3
+    # S = 4,000,000 < block: tensor by tensor; fc.weight (2,359,296) does not fit behind 2,366,440 and opens chunk 1
+    place, n_chunks, _ = L.layout_grouped(sizes, gids, 4_000_000)
+    assert place[8] == (0, 2_365_672) and place[9] == (1, 0) and place[10] == (1, 2_359_296)
+    assert place[11] == (2, 0) and place[12] == (2, 2_359_296) and place[13] == (2, 2_360_064) and n_chunks == 3
 
 
 def test_search_is_the_brute_force_minimum():
