@@ -238,6 +238,30 @@ int pt_chunk_unpack(pt_ctx* ctx, const pt_pack_plan* plan, const void* const* ch
 int pt_chunk_grad_sqnorm(pt_ctx* ctx, const void* const* grad_chunks, uint32_t first_chunk,
                          uint32_t n_chunks, int finalize, void* stream);
 
+/* The global gradient norm for callers that cannot allocate: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Computes what pt_chunk_grad_sqnorm(grad_chunks, 0,
+ * n_chunks, finalize) computes - same kernels, same fixed reduction order, the same bits - without a
+ * context: the block partials and per-chunk sums live in a file-scope device array of the library
+ * (6.05 MiB per GPU, held until the process ends) instead of memory a context allocated.  Calls no
+ * hipMalloc / hipFree and no allocating routine; enqueues three kernels on `stream` and returns.
+ *   grad_arena       device: n_chunks gradient chunks of chunk_elems 16-bit words each, back to back
+ *                    (chunk c starts at element c * chunk_elems); 16-byte aligned; read only
+ *   dtype            PT_BF16 or PT_FP16 (how the words decode)
+ *   loss_scale       every value is divided by it before it is squared (1 for unscaled gradients)
+ *   out_sqnorm_norm  device, two doubles written by the last kernel: [0] = sum of (g/loss_scale)^2,
+ *                    [1] = its square root
+ *   out_found_inf    device, one int32 written by the last kernel: 1 if any word is +-inf or NaN
+ * Limits: n_chunks <= 4096 and n_chunks * ceil(chunk_elems / 32768) <= 2^19 (2^34 elements when chunks
+ * are multiples of 32768: the LLaMA-7B and -13B states fit); beyond that PT_ERR_UNSUPPORTED, nothing is
+ * launched.  Errors have no context: their text is pt_last_error(NULL) of the calling thread.
+ * All calls on one GPU share the one scratch array: calls that overlap in time on one GPU (two
+ * streams, two threads) race; order them.  The array keeps the last call's contents; every launch
+ * overwrites all the entries the next launch reads, so nothing needs clearing.  The array's device
+ * address is looked up once per device (hipGetSymbolAddress), by pt_ctx_create or by the first call
+ * of this function on that device - make that first call outside a graph capture. */
+int pt_chunk_grad_sqnorm_noalloc(const void* grad_arena, int dtype, uint64_t chunk_elems, uint32_t n_chunks,
+                                 double loss_scale, double* out_sqnorm_norm, int32_t* out_found_inf, void* stream);
+
 /* Update of GPU-resident ("persistent") chunks (paper: persistent chunks reside
  * on the GPU and are updated there; Appendix A.1 T_GPU_OPTIM).  For every element
  * of chunks [first_chunk, first_chunk+n_chunks), padding included:

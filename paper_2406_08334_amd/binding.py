@@ -23,6 +23,7 @@ EXPORTS = [
     "pt_step_report_read", "pt_update_consts_read", "pt_step_override", "pt_calib_copy", "pt_ctx_set_option",
     "pt_layout_grouped", "pt_chunk_size_search", "pt_chunk_host_adamw_step",
     "pt_optim_predict", "pt_optim_choose", "pt_ctx_set_no_decay", "pt_chunk_accum_grads",
+    "pt_chunk_grad_sqnorm_noalloc",
 ]
 
 
@@ -105,6 +106,7 @@ def lib():
         L.pt_chunk_unpack.argtypes = [vp, vp, pp, vp]
         L.pt_chunk_accum_grads.argtypes = [vp, vp, pp, C.c_int, C.c_int, vp]
         L.pt_chunk_grad_sqnorm.argtypes = [vp, pp, u32, u32, C.c_int, vp]
+        L.pt_chunk_grad_sqnorm_noalloc.argtypes = [vp, C.c_int, u64, u32, C.c_double, vp, vp, vp]
         L.pt_chunk_adamw_step.argtypes = [vp, C.POINTER(pt_hparams), u32, u32, pp, pp, pp, pp, pp, vp]
         L.pt_stream_reserve.argtypes = [vp, u32]
         L.pt_chunk_stream_step.argtypes = [vp, C.POINTER(pt_hparams), u32, u32, pp, pp, pp, pp, pp, vp]
@@ -240,6 +242,15 @@ def pt_chunk_unpack(ctx, plan, chunks, stream=None):
 def pt_chunk_grad_sqnorm(ctx, grad_chunks, first_chunk: int, n_chunks: int, finalize: bool, stream=None):
     _check(lib().pt_chunk_grad_sqnorm(ctx, _ptr_array(grad_chunks), int(first_chunk), int(n_chunks),
                                       1 if finalize else 0, _stream(stream)), "pt_chunk_grad_sqnorm", ctx)
+
+
+def pt_chunk_grad_sqnorm_noalloc(grad_arena, dtype: int, chunk_elems: int, n_chunks: int, loss_scale: float,
+                                 out_sqnorm_norm, out_found_inf, stream=None):
+    """grad_arena: device tensor holding the chunks back to back; out_sqnorm_norm: device float64[2];
+    out_found_inf: device int32[1].  Allocates nothing."""
+    _check(lib().pt_chunk_grad_sqnorm_noalloc(_addr(grad_arena), int(dtype), int(chunk_elems), int(n_chunks),
+                                              float(loss_scale), _addr(out_sqnorm_norm), _addr(out_found_inf),
+                                              _stream(stream)), "pt_chunk_grad_sqnorm_noalloc")
 
 
 def pt_chunk_adamw_step(ctx, hp: pt_hparams, first_chunk: int, n_chunks: int, grad, master, m, v, param16,

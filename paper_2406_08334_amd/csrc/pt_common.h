@@ -212,6 +212,10 @@ int pt_launch_adamw(pt_ctx* ctx, uint32_t first_col, uint32_t n_cols, hipStream_
                     uint32_t mask_chunk0, bool zero_grads);
 
 // ---- implemented in pt_norm.hip ---------------------------------------------------------
+// Looks up (once per device) the device address of the file-scope scratch array that
+// pt_chunk_grad_sqnorm_noalloc works in; out may be NULL.  Called by pt_ctx_create, so that a process
+// with a context never pays the lookup inside a hot call.
+int pt_static_scratch_setup(void** out);
 // Sums per-block partials into per-chunk values.  uniform mode (tile_begin == NULL):
 // chunk first+i owns partials [i*per_chunk, (i+1)*per_chunk).
 int pt_launch_chunk_reduce(pt_ctx* ctx, const double* part, const uint32_t* flag,

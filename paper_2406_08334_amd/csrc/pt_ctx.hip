@@ -117,6 +117,7 @@ static void ctx_free_all(pt_ctx* ctx) {
 
 static int ctx_alloc(pt_ctx* ctx, const pt_scaler_cfg* sc) {
   PT_HIP(ctx, hipGetDevice(&ctx->device));
+  if (int rc = pt_static_scratch_setup(nullptr); rc != PT_OK) return pt_fail(ctx, rc, "%s", pt_last_error(nullptr));
   PT_HIP(ctx, hipMalloc(&ctx->d_state, sizeof(PtDevState)));
   size_t tab_bytes = size_t(N_ROWS) * ctx->table_cols * sizeof(uint64_t);
   PT_HIP(ctx, hipMalloc(&ctx->d_table, tab_bytes));

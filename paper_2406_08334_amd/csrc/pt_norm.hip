@@ -11,6 +11,8 @@
 
 #include <hip/hip_fp16.h>
 
+#include <mutex>
+
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -228,5 +230,134 @@ extern "C" int pt_chunk_grad_sqnorm(pt_ctx* ctx, const void* const* grad_chunks,
     ctx->norm_finalized = true;
     ctx->prepared = false;
   }
+  return PT_OK;
+}
+
+// ---- the norm for callers that cannot allocate -------------------------------------------------
+// Same kernels and the same reduction order as pt_chunk_grad_sqnorm(grad_chunks, ..., finalize), but
+// without a context: the block partials and per-chunk sums live in one file-scope device array
+// instead of memory a context allocated, and the gradient chunks are addressed as one arena.
+
+namespace {
+
+constexpr uint32_t PT_STATIC_MAX_PARTIALS = 1u << 19;   // blocks of PT_NORM_BLOCK_ELEMS elements: 2^34 elements
+constexpr uint32_t PT_STATIC_MAX_CHUNKS = 4096;
+constexpr int PT_STATIC_MAX_DEVICES = 64;
+
+struct PtStaticScratch {
+  double part[PT_STATIC_MAX_PARTIALS];
+  uint32_t flag[PT_STATIC_MAX_PARTIALS];
+  double chunk_sq[PT_STATIC_MAX_CHUNKS];
+  uint32_t chunk_flag[PT_STATIC_MAX_CHUNKS];
+};
+
+}  // namespace
+
+// 6.05 MiB per GPU the library runs on, held until the process ends.  In host code this name is only a
+// stand-in for the symbol: the device address comes from hipGetSymbolAddress (scratch_of_current_device).
+static __device__ __align__(256) unsigned char scratch[sizeof(PtStaticScratch)];
+
+namespace {
+
+// As k_sqnorm, for chunks that lie back to back in one arena; the loss scale comes by value.
+template <int DT>
+__global__ void __launch_bounds__(NB_THREADS)
+k_sqnorm_arena(const void* __restrict__ arena, uint64_t S, double loss_scale, double* __restrict__ part,
+               uint32_t* __restrict__ flagout) {
+  const uint32_t b = blockIdx.x, i = blockIdx.y;
+  const PT_GLOBAL u32x4* base = (const PT_GLOBAL u32x4*)((uint64_t)(uintptr_t)arena + 2ull * S * i);
+  double acc;
+  uint32_t flag;
+  sqnorm_block<DT>(base, S, b, 1.0 / loss_scale, acc, flag);
+  if (threadIdx.x == 0) {
+    size_t slot = size_t(i) * gridDim.x + b;
+    part[slot] = acc;
+    flagout[slot] = flag;
+  }
+}
+
+// As k_finalize, into the caller's outputs.
+__global__ void k_finalize_out(const double* __restrict__ chunk_sq, const uint32_t* __restrict__ chunk_flag,
+                               uint32_t C, double* __restrict__ out_sq_norm, int32_t* __restrict__ out_found_inf) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  double t = 0.0;
+  uint32_t f = 0;
+  for (uint32_t c = 0; c < C; ++c) { t += chunk_sq[c]; f |= chunk_flag[c]; }
+  out_sq_norm[0] = t;
+  out_sq_norm[1] = sqrt(t);
+  *out_found_inf = f ? 1 : 0;
+}
+
+std::mutex g_scratch_mutex;
+void* g_scratch_addr[PT_STATIC_MAX_DEVICES] = {};
+
+}  // namespace
+
+// Device address of `scratch` on the current device, looked up once per device (every GPU holds its
+// own copy of the array at its own address).
+int pt_static_scratch_setup(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return pt_fail(nullptr, PT_ERR_HIP, "hipGetDevice failed: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= PT_STATIC_MAX_DEVICES)
+    return pt_fail(nullptr, PT_ERR_UNSUPPORTED, "device %d: at most %d devices are supported", dev, PT_STATIC_MAX_DEVICES);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_addr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p)
+      return pt_fail(nullptr, PT_ERR_HIP, "hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+    g_scratch_addr[dev] = p;
+  }
+  if (out) *out = g_scratch_addr[dev];
+  return PT_OK;
+}
+
+extern "C" int pt_chunk_grad_sqnorm_noalloc(const void* grad_arena, int dtype, uint64_t chunk_elems, uint32_t n_chunks,
+                                            double loss_scale, double* out_sqnorm_norm, int32_t* out_found_inf,
+                                            void* stream) {
+  if (!grad_arena || !out_sqnorm_norm || !out_found_inf)
+    return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_chunk_grad_sqnorm_noalloc: NULL pointer");
+  if (dtype != PT_BF16 && dtype != PT_FP16)
+    return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_chunk_grad_sqnorm_noalloc: dtype %d is neither PT_BF16 nor PT_FP16", dtype);
+  if (chunk_elems == 0 || n_chunks == 0)
+    return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_chunk_grad_sqnorm_noalloc: chunk_elems and n_chunks must be > 0");
+  if (chunk_elems % 8 != 0 || (reinterpret_cast<uintptr_t>(grad_arena) & 15u))
+    return pt_fail(nullptr, PT_ERR_ALIGNMENT,
+                   "pt_chunk_grad_sqnorm_noalloc: chunk_elems must be a multiple of 8 and the arena 16-byte aligned");
+  if ((reinterpret_cast<uintptr_t>(out_sqnorm_norm) & 7u) || (reinterpret_cast<uintptr_t>(out_found_inf) & 3u))
+    return pt_fail(nullptr, PT_ERR_ALIGNMENT, "pt_chunk_grad_sqnorm_noalloc: misaligned output pointer");
+  if (!(loss_scale >= 1.0) || !(loss_scale <= 1.8446744073709552e19))
+    return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_chunk_grad_sqnorm_noalloc: loss_scale must be in [1, 2^64]");
+  const uint64_t blocks_per_chunk = (chunk_elems + PT_NORM_BLOCK_ELEMS - 1) / PT_NORM_BLOCK_ELEMS;
+  if (n_chunks > PT_STATIC_MAX_CHUNKS || blocks_per_chunk * n_chunks > PT_STATIC_MAX_PARTIALS)
+    return pt_fail(nullptr, PT_ERR_UNSUPPORTED,
+                   "pt_chunk_grad_sqnorm_noalloc: %u chunks of %llu elements exceed the static scratch (at most %u chunks "
+                   "and %u blocks of %u elements, i.e. 2^34 elements); use pt_chunk_grad_sqnorm with a context",
+                   n_chunks, (unsigned long long)chunk_elems, PT_STATIC_MAX_CHUNKS, PT_STATIC_MAX_PARTIALS,
+                   PT_NORM_BLOCK_ELEMS);
+  void* base = nullptr;
+  int rc = pt_static_scratch_setup(&base);
+  if (rc != PT_OK) return rc;
+  // every address below derives from the looked-up device address, never from the array's name
+  PtStaticScratch* sc = static_cast<PtStaticScratch*>(base);
+  hipStream_t st = (hipStream_t)stream;
+  dim3 grid((uint32_t)blocks_per_chunk, n_chunks);
+  // Nothing here has to start at zero: each launch writes every partial and per-chunk slot that the
+  // next one reads (n_chunks * blocks_per_chunk partials, n_chunks sums), so stale contents of an
+  // earlier, larger call are never read.
+  if (dtype == PT_BF16)
+    hipLaunchKernelGGL(k_sqnorm_arena<PT_BF16>, grid, dim3(NB_THREADS), 0, st, grad_arena, chunk_elems, loss_scale,
+                       sc->part, sc->flag);
+  else
+    hipLaunchKernelGGL(k_sqnorm_arena<PT_FP16>, grid, dim3(NB_THREADS), 0, st, grad_arena, chunk_elems, loss_scale,
+                       sc->part, sc->flag);
+  if (hipGetLastError() != hipSuccess) return pt_fail(nullptr, PT_ERR_HIP, "pt_chunk_grad_sqnorm_noalloc: launch of k_sqnorm_arena failed");
+  hipLaunchKernelGGL(k_chunk_reduce, dim3(n_chunks), dim3(NB_THREADS), 0, st, sc->part, sc->flag,
+                     (const uint32_t*)nullptr, 0u, (uint32_t)blocks_per_chunk, sc->chunk_sq, sc->chunk_flag);
+  if (hipGetLastError() != hipSuccess) return pt_fail(nullptr, PT_ERR_HIP, "pt_chunk_grad_sqnorm_noalloc: launch of k_chunk_reduce failed");
+  hipLaunchKernelGGL(k_finalize_out, dim3(1), dim3(64), 0, st, sc->chunk_sq, sc->chunk_flag, n_chunks, out_sqnorm_norm,
+                     out_found_inf);
+  if (hipGetLastError() != hipSuccess) return pt_fail(nullptr, PT_ERR_HIP, "pt_chunk_grad_sqnorm_noalloc: launch of k_finalize_out failed");
   return PT_OK;
 }
