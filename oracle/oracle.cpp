@@ -30,9 +30,12 @@
 // closed forms and power-of-two scaling; AdamW vs closed forms, a 60-digit
 // decimal evaluation and torch.optim.AdamW in fp64; pack vs per-element brute
 // force and the round-trip invariant; the loss-scale machine vs a replay without
-// the skipped step.  orc_adamw_f32seq (the fp32 operation sequence) is pinned
-// bit for bit on a case where no operation rounds (exact rationals) and otherwise only through
-// its distance to orc_adamw_f64: its last bits in general are PARITY UNPINNED.  The fp32 gradient-accumulation variant
+// the skipped step.  orc_adamw_f32seq (the fp32 operation sequence) is pinned bit for bit, in
+// the general case where operations round, against the same sequence carried out in exact
+// rational arithmetic with one value-domain nearest/ties-to-even rounding per operation
+// (Python integers and fractions; square roots proven by exact squares), on 16-bit and on
+// fp32 gradients, subnormal intermediates included; it also stays within tolerance of
+// orc_adamw_f64.  The fp32 gradient-accumulation variant
 // (orc_accum_f32, orc_sqnorm_f32, orc_*_g32): numpy float32 addition and exact rationals,
 // math.fsum, bit-identity with the 16-bit-gradient functions on decoded words, a closed form
 // on gradients no 16-bit word holds, torch.optim.AdamW in fp64 on accumulated gradients.

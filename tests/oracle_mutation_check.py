@@ -22,6 +22,17 @@ MUTATIONS = [
     ("fp32 sequence: (1 - beta1) replaced by beta1", "float t1 = omb1 * g;", "float t1 = b1 * g;"),
     ("fp32 sequence: decay also on undecayed elements",
      "float t3 = w[i] * ((no_decay && no_decay[i]) ? 1.0f : decay);", "float t3 = w[i] * decay;"),
+    # last-bit variations of the fp32 sequence: only a correctly rounded referee can tell them apart
+    ("fp32 sequence: momentum with two roundings instead of one fused multiply-add",
+     "float mn = std::fmaf(b1, m[i], t1);", "float mn = b1 * m[i] + t1;"),
+    ("fp32 sequence: (1 - beta2) * (g * g) instead of ((1 - beta2) * g) * g",
+     "float t2 = omb2 * g;\n      t2 = t2 * g;", "float t2 = g * g;\n      t2 = omb2 * t2;"),
+    ("fp32 sequence: denominator with two roundings", "float d = std::fmaf(std::sqrt(vn), rsb2, eps);",
+     "float d = std::sqrt(vn) * rsb2 + eps;"),
+    ("fp32 sequence: weight update with two roundings", "float wn = std::fmaf(-step_size, u, t3);",
+     "float wn = t3 - step_size * u;"),
+    ("fp32 sequence: multiplies by the reciprocal of the denominator instead of dividing", "float u = mn / d;",
+     "float u = mn * (1.0f / d);"),
     ("norm ignores the loss scale", "double x = double(decode16(g[i], dtype)) / loss_scale;",
      "double x = double(decode16(g[i], dtype));"),
     ("clip coefficient without its epsilon", "max_norm / (norm + 1e-6)", "max_norm / norm"),

@@ -411,3 +411,179 @@ def test_f32_sequence_is_exact_where_every_operation_is_exact(orc):
         want = F(int(j[i]), 64) * (1 - F(1, 2 ** 11)) - F(1, 2 ** 9) * ((g / 2) / d)
         assert F(float(w[i])) == want
     assert np.array_equal(p16, orc.encode16_rne(w, orc.BF16))
+
+
+# ------------------------------------------------ the fp32 sequence against exact rational arithmetic
+# An independent referee for orc_adamw_f32seq in the general case (operations that DO round): every
+# operation of the sequence is carried out exactly on rationals and then rounded once to binary32 by a
+# value-domain nearest / ties-to-even rule written here (no float type, no C compiler, no libm takes part:
+# Python integers and fractions only), the square root through integer square roots with the result
+# proven by exact squares of the neighbouring midpoints.
+
+from fractions import Fraction as Fr
+from math import isqrt
+
+
+def _floor_log2(a: Fr) -> int:
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fr(2) ** e > a:
+        e -= 1
+    if Fr(2) ** (e + 1) <= a:
+        e += 1
+    assert Fr(2) ** e <= a < Fr(2) ** (e + 1)
+    return e
+
+
+def _quantum(a: Fr, p: int, emin: int) -> Fr:
+    """spacing of the format (p significand bits, smallest normal exponent emin) at magnitude a > 0"""
+    return Fr(2) ** (max(_floor_log2(a), emin) - (p - 1))
+
+
+def rn(x: Fr, p: int = 24, emin: int = -126, emax: int = 127) -> Fr:
+    """nearest value of the binary format, ties to the even significand; subnormals included"""
+    if x == 0:
+        return x
+    a = abs(x)
+    q = _quantum(a, p, emin)
+    k = a / q
+    n = k.numerator // k.denominator
+    r = k - n
+    if r > Fr(1, 2) or (r == Fr(1, 2) and n % 2 == 1):
+        n += 1
+    out = n * q
+    assert out < Fr(2) ** (emax + 1), "overflow is not part of these cases"
+    return out if x > 0 else -out
+
+
+def rn_sqrt(x: Fr) -> Fr:
+    """correctly rounded binary32 square root of a non-negative rational"""
+    if x == 0:
+        return x
+    K = 160
+    y = Fr(isqrt((x.numerator << (2 * K)) // x.denominator), 1 << K)      # floor(sqrt(x) * 2^K) / 2^K
+    r = rn(y)
+    for cand in (r, r - _quantum(r, 24, -126), r + _quantum(r, 24, -126)):
+        if cand <= 0:
+            continue
+        q = _quantum(cand, 24, -126)
+        lo_q = q / 2 if cand == Fr(2) ** _floor_log2(cand) and _floor_log2(cand) > -126 else q
+        lo, hi = cand - lo_q / 2, cand + q / 2
+        if lo * lo < x < hi * hi:             # a square root of a binary32 value never sits on a midpoint
+            return cand
+    raise AssertionError("no candidate brackets the square root")
+
+
+def decode_word(w: int, fbits: int, ebits: int) -> Fr:
+    """IEEE definition of a 16-bit word: 1 sign bit, ebits exponent bits, fbits fraction bits"""
+    sign = -1 if (w >> 15) & 1 else 1
+    E = (w >> fbits) & ((1 << ebits) - 1)
+    f = w & ((1 << fbits) - 1)
+    bias = (1 << (ebits - 1)) - 1
+    assert E != (1 << ebits) - 1, "finite words only"
+    if E == 0:
+        return sign * Fr(f, 1 << fbits) * Fr(2) ** (1 - bias)
+    return sign * (1 + Fr(f, 1 << fbits)) * Fr(2) ** (E - bias)
+
+
+def word16_of(x: Fr, fp16: bool) -> int:
+    """bit pattern of the 16-bit value nearest to x (ties to even), from the value alone"""
+    p, emin, fbits, ebits = (11, -14, 10, 5) if fp16 else (8, -126, 7, 8)
+    r = rn(x, p, emin, 15 if fp16 else 127)
+    if r == 0:
+        return 0x8000 if x < 0 else 0
+    a = abs(r)
+    e = _floor_log2(a)
+    bias = (1 << (ebits - 1)) - 1
+    if e < emin:
+        E, f = 0, a / Fr(2) ** (emin - fbits)
+    else:
+        E, f = e + bias, (a / Fr(2) ** e - 1) * (1 << fbits)
+    assert f.denominator == 1
+    return (0x8000 if r < 0 else 0) | (E << fbits) | int(f)
+
+
+def seq_exact(c, g, w, m, v, decay_on):
+    """the fp32 operation sequence, every operation rounded once from its exact result"""
+    b1, b2, omb1, omb2, decay, step_size, rsb2, eps, gm = c
+    gg = rn(g * gm)
+    t1 = rn(omb1 * gg)
+    mn = rn(b1 * m + t1)
+    t2 = rn(omb2 * gg)
+    t2 = rn(t2 * gg)
+    vn = rn(b2 * v + t2)
+    d = rn(rn_sqrt(vn) * rsb2 + eps)
+    u = rn(mn / d)
+    t3 = rn(w * (decay if decay_on else 1))
+    wn = rn(-step_size * u + t3)
+    return wn, mn, vn
+
+
+@pytest.mark.parametrize("fp16", [False, True])
+def test_f32_sequence_against_correctly_rounded_rational_arithmetic(orc, fp16):
+    n, steps = 700, 3
+    dt, odt = (torch.float16, orc.FP16) if fp16 else (torch.bfloat16, orc.BF16)
+    fbits, ebits = (10, 5) if fp16 else (7, 8)
+    sigma = 65536.0 if fp16 else 1.0
+    h = hp()
+    p = synth.normal_16(synth.SEED_PARAMS + 3, 0, 0, 0, n, 0.02, dt, "cpu")
+    p16 = synth.as_u16(p).copy()
+    w = p.float().numpy().copy()
+    m, v = np.zeros(n, np.float32), np.zeros(n, np.float32)
+    mask = (np.arange(n) % 5 == 0).astype(np.uint8)                     # every fifth element is not decayed
+    W = [Fr(float(x)) for x in w]
+    M = [Fr(0)] * n
+    V = [Fr(0)] * n
+    for t in range(1, steps + 1):
+        g = synth.normal_16(synth.SEED_GRADS + 3, t, 0, 0, n, 1e-3, dt, "cpu", scale=sigma)
+        g16 = synth.as_u16(g).copy()
+        # a few special gradients: zero, the smallest subnormal word, and (bf16) values whose square is subnormal in fp32
+        g16[0], g16[1], g16[2] = 0, 1, 0x8001
+        if not fp16:
+            g16[3:9] = bf16w(np.array([3e-18, -7e-19, 2.5e-20, -1e-21, 6e-17, 1e-30], np.float32))
+        gm = 0.0123 / sigma * (1.0 + 0.1 * t)
+        c = orc.consts_f32(h, t, gm)
+        cF = [Fr(float(x)) for x in c]
+        orc.adamw_f32seq(c, g16, w, m, v, p16, odt, threads=2, no_decay=mask)
+        for i in range(n):
+            W[i], M[i], V[i] = seq_exact(cF, decode_word(int(g16[i]), fbits, ebits), W[i], M[i], V[i], not mask[i])
+        assert [Fr(float(x)) for x in w] == W, f"master weights, step {t}"
+        assert [Fr(float(x)) for x in m] == M, f"momentum, step {t}"
+        assert [Fr(float(x)) for x in v] == V, f"variance, step {t}"
+        assert [int(x) for x in p16] == [word16_of(x, fp16) for x in W], f"16-bit parameters, step {t}"
+    if not fp16:
+        assert any(0 < x < Fr(2) ** -126 for x in V), "the case must reach subnormal variances"
+
+
+def test_f32_sequence_on_fp32_gradients_against_rational_arithmetic(orc):
+    """the same referee for the fp32-gradient variant: gradients that no 16-bit word holds"""
+    n = 400
+    rng = np.random.default_rng(11)
+    g32 = (rng.standard_normal(n) * 4e-3).astype(np.float32)
+    g32[:4] = [0.0, 1e-30, -3e-39, 1.5e-19]                              # zero, tiny, subnormal, subnormal square
+    w = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    m = (rng.standard_normal(n) * 1e-5).astype(np.float32)
+    v = (rng.random(n) * 1e-10).astype(np.float32)
+    p16 = np.zeros(n, np.uint16)
+    c = orc.consts_f32(hp(), 7, 0.0371)
+    cF = [Fr(float(x)) for x in c]
+    want = [seq_exact(cF, Fr(float(g32[i])), Fr(float(w[i])), Fr(float(m[i])), Fr(float(v[i])), True) for i in range(n)]
+    orc.adamw_f32seq_g32(c, g32, w, m, v, p16, orc.BF16, threads=1)
+    assert [Fr(float(x)) for x in w] == [x[0] for x in want]
+    assert [Fr(float(x)) for x in m] == [x[1] for x in want]
+    assert [Fr(float(x)) for x in v] == [x[2] for x in want]
+    assert [int(x) for x in p16] == [word16_of(x[0], False) for x in want]
+
+
+def test_the_rational_referee_itself():
+    """rn / rn_sqrt / word16_of on values whose rounding is known by hand"""
+    assert rn(Fr(1) + Fr(1, 2 ** 24)) == 1                               # tie -> even
+    assert rn(Fr(1) + Fr(3, 2 ** 24)) == 1 + Fr(1, 2 ** 22)              # tie -> even (upwards)
+    assert rn(Fr(1) + Fr(1, 2 ** 24) + Fr(1, 2 ** 60)) == 1 + Fr(1, 2 ** 23)
+    assert rn(Fr(3, 2 ** 151)) == Fr(1, 2 ** 149)                        # 0.75 of the smallest subnormal
+    assert rn(Fr(1, 2 ** 150)) == 0 and rn(Fr(3, 2 ** 150)) == Fr(2, 2 ** 149)   # subnormal ties -> even
+    assert rn_sqrt(Fr(4)) == 2 and rn_sqrt(Fr(2)) == Fr(11863283, 2 ** 23)        # 1.41421354...
+    assert rn_sqrt(Fr(1, 2 ** 149)) == rn(Fr(isqrt(2 << 300), 1 << 150) * Fr(1, 2 ** 75))
+    assert word16_of(Fr(1) + Fr(1, 256), False) == 0x3F80                # bf16 tie -> even
+    assert word16_of(Fr(1) + Fr(3, 256), False) == 0x3F82
+    assert word16_of(Fr(1, 2 ** 24), True) == 0x0001 and word16_of(Fr(-1, 2 ** 25), True) == 0x8000
+    assert word16_of(Fr(65504), True) == 0x7BFF
