@@ -146,9 +146,11 @@ int pt_ctx_set_no_decay(pt_ctx* ctx, const pt_segment* segs, uint32_t n_segs);
  *                   chunk buffers grow to 18 bytes per element; PT_ERR_STATE afterwards) and
  *                   before pt_pack_plan_create (plans are tiled for the kernel they feed).
  *   "adamw_zero_grads"  1 = pt_chunk_adamw_step overwrites every gradient element it has read
- *                   with zero (for callers whose backward pass adds into the chunks); not on a
- *                   skipped step.  The streamed and host-side updates never write gradients:
- *                   their host copies are overwritten by the next offload. */
+ *                   with zero (for callers whose backward pass adds into the chunks).  A skipped
+ *                   step zeroes them too: the non-finite value that caused the skip must not stay
+ *                   in the sums, or every later step would be skipped as well.  The streamed and
+ *                   host-side updates never write gradients: their host copies are overwritten by
+ *                   the next offload. */
 int pt_ctx_set_option(pt_ctx* ctx, const char* name, int64_t value);
 
 /* ---- layout (host, integer only) ---------------------------------------------------

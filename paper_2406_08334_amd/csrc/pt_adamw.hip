@@ -143,8 +143,10 @@ __device__ __forceinline__ void update_unit(const Consts& k, const float (&dk)[4
 
 // One flat index space of tiles (256 x UNROLL units of 4 elements) over all chunks of
 // the launch: tile T belongs to chunk T / tiles_per_chunk.  Block b takes tiles
-// b, b + gridDim.x, ...  A block's consecutive tiles mostly stay in one chunk, so the
-// five base pointers are re-read from the table only when the chunk changes.
+// b, b + gridDim.x, ...  With the default grid (a third of the tiles) a block's two or three
+// tiles lie a third of the launch apart, in different chunks, so the five base pointers are
+// re-read from the table for nearly every tile (five uniform loads against 28 KiB or more of
+// traffic per tile); a small grid keeps consecutive tiles in one chunk and skips the re-read.
 //
 // MASKED: some element ranges of some chunks are kept out of the weight decay (sorted,
 // disjoint ranges per chunk: nd_begin[c] .. nd_begin[c+1] index pairs (lo, hi) in nd_ranges).
@@ -153,7 +155,8 @@ __device__ __forceinline__ void update_unit(const Consts& k, const float (&dk)[4
 //
 // GF32: the gradient chunks hold fp32 (accumulated micro-batches) instead of 16-bit words.
 // zero_grads: every gradient element is overwritten with zero once it has been read (for
-// callers whose backward pass adds into the chunk); not on a skipped step.
+// callers whose backward pass adds into the chunk); a skipped step zeroes them as well (store-only
+// pass), so that the non-finite value that caused the skip does not stay in the sums.
 template <int DT, int UNROLL, bool NT, bool MASKED, bool GF32>
 __global__ void __launch_bounds__(AW_THREADS)
 k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_col, uint32_t n_cols,
@@ -183,6 +186,17 @@ k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_
           p.y = encode16<DT>(w[2]) | (encode16<DT>(w[3]) << 16);
           pq[u] = p;
         }
+      }
+    }
+    // The gradients are zeroed on a skipped step too: a caller whose backward pass ADDS into the
+    // chunks would otherwise carry the inf/NaN that caused the skip into every later sum.
+    if (zero_grads) {
+      for (uint32_t T = blockIdx.x; T < total_tiles; T += gridDim.x) {
+        const uint32_t ci = T / tiles_per_chunk, tile = T - ci * tiles_per_chunk;
+        g_ptr gq = (g_ptr)(table[size_t(ROW_GRAD) * table_cols + first_col + ci]);
+        const uint64_t u_end = min(units, (uint64_t(tile) + 1) * TILE_UNITS);
+        for (uint64_t u = uint64_t(tile) * TILE_UNITS + threadIdx.x; u < u_end; u += AW_THREADS)
+          st_stream<NT>(gzero, gq + u);
       }
     }
     return;
