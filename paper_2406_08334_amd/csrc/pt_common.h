@@ -78,6 +78,8 @@ struct pt_pack_plan {
   std::vector<uint32_t> touched;           // chunks that own at least one tile
 };
 
+namespace pt_host { class Pool; }
+
 struct pt_ctx {
   int device = 0;
   int dtype = PT_BF16;
@@ -127,6 +129,8 @@ struct pt_ctx {
   hipStream_t s_scalar = nullptr;
   hipEvent_t ev_scalar = nullptr;
   PtDevState* h_state = nullptr;
+  pt_host::Pool* host_pool = nullptr;   // worker threads of the host-side update, started on first use
+  uint32_t host_pool_threads = 0;       // n_threads the pool was built for
 
   std::string err;
 };
@@ -210,6 +214,10 @@ int pt_prepare_consts(pt_ctx* ctx, const pt_hparams* hp, hipStream_t stream);
 // zero_grads: overwrite the gradient chunks with zeros once read (resident chunks only).
 int pt_launch_adamw(pt_ctx* ctx, uint32_t first_col, uint32_t n_cols, hipStream_t stream, bool recast_on_skip,
                     uint32_t mask_chunk0, bool zero_grads);
+
+// ---- implemented in pt_host.hip ------------------------------------------------------------
+// Stops and joins the context's worker threads (no-op when there are none).
+void pt_host_pool_destroy(pt_ctx* ctx);
 
 // ---- implemented in pt_norm.hip ---------------------------------------------------------
 // Looks up (once per device) the device address of the file-scope scratch array that

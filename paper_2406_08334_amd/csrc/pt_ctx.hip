@@ -92,6 +92,7 @@ extern "C" const char* pt_last_error(const pt_ctx* ctx) {
 // ---- public: context ----------------------------------------------------------------------
 
 static void ctx_free_all(pt_ctx* ctx) {
+  pt_host_pool_destroy(ctx);
   if (ctx->s_up) (void)hipStreamDestroy(ctx->s_up);
   if (ctx->s_comp) (void)hipStreamDestroy(ctx->s_comp);
   if (ctx->s_down) (void)hipStreamDestroy(ctx->s_down);

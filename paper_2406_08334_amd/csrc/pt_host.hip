@@ -6,102 +6,17 @@
 //
 // Same fp32 operation sequence as the device kernel, driven by the same nine fp32
 // constants (read back from the device once per step), so host-updated and
-// device-updated chunks are bit-identical.  The loop is plain scalar code that the
-// compiler vectorises per x86 target (AVX-512 / AVX2 clones picked at load time).
+// device-updated chunks are bit-identical.  The loops, the grain queue and the thread pool
+// are plain host C++ in pt_host_update.h; this file is the entry point around them.
 #include "pt_common.h"
-
-#include <algorithm>
-#include <atomic>
-#include <cmath>
-#include <thread>
+#include "pt_host_update.h"
 
 #pragma clang fp contract(off)
 
-namespace {
-
-struct HostConsts { float b1, b2, omb1, omb2, decay, step_size, rsb2, eps, gm; };
-
-inline float bf16_to_f32(uint16_t w) {
-  uint32_t u = uint32_t(w) << 16;
-  float f;
-  std::memcpy(&f, &u, 4);
-  return f;
+void pt_host_pool_destroy(pt_ctx* ctx) {
+  delete ctx->host_pool;
+  ctx->host_pool = nullptr;
 }
-
-inline uint16_t f32_to_bf16(float x) {
-  uint32_t u;
-  std::memcpy(&u, &x, 4);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return uint16_t((u >> 16) | 0x0040u);
-  return uint16_t((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
-}
-
-inline float fp16_to_f32(uint16_t w) {
-  _Float16 h;
-  std::memcpy(&h, &w, 2);
-  return float(h);
-}
-
-inline uint16_t f32_to_fp16(float x) {
-  _Float16 h = _Float16(x);           // round to nearest even (the default rounding mode)
-  uint16_t w;
-  std::memcpy(&w, &h, 2);
-  return w;
-}
-
-#define PT_HOST_UPDATE_BODY(DECODE, ENCODE)                                         \
-  for (uint64_t i = 0; i < n; ++i) {                                               \
-    float gg = DECODE(g[i]) * k.gm;                                                \
-    float t1 = k.omb1 * gg;                                                        \
-    float mn = std::fmaf(k.b1, m[i], t1);                                          \
-    float t2 = k.omb2 * gg;                                                        \
-    t2 = t2 * gg;                                                                  \
-    float vn = std::fmaf(k.b2, v[i], t2);                                          \
-    float d = std::fmaf(std::sqrt(vn), k.rsb2, k.eps);                             \
-    float u = mn / d;                                                              \
-    float t3 = w[i] * k.decay;                                                     \
-    float wn = std::fmaf(-k.step_size, u, t3);                                     \
-    m[i] = mn; v[i] = vn; w[i] = wn;                                               \
-    p[i] = ENCODE(wn);                                                             \
-  }
-
-// x86 clones picked at load time; the device pass of the compiler only parses this host code
-// and does not know function multiversioning, so it sees the plain declaration.
-#if defined(__HIP_DEVICE_COMPILE__)
-#define PT_HOST_CLONES
-#else
-#define PT_HOST_CLONES __attribute__((target_clones("arch=x86-64-v4", "arch=x86-64-v3", "default")))
-#endif
-
-PT_HOST_CLONES
-void host_update_bf16(const HostConsts k, const uint16_t* __restrict__ g, float* __restrict__ w,
-                      float* __restrict__ m, float* __restrict__ v, uint16_t* __restrict__ p, uint64_t n) {
-  PT_HOST_UPDATE_BODY(bf16_to_f32, f32_to_bf16)
-}
-
-inline float f32_identity(float x) { return x; }
-
-// fp32 gradient chunks (accumulated micro-batches): the gradient is read as it is
-PT_HOST_CLONES
-void host_update_bf16_g32(const HostConsts k, const float* __restrict__ g, float* __restrict__ w,
-                          float* __restrict__ m, float* __restrict__ v, uint16_t* __restrict__ p, uint64_t n) {
-  PT_HOST_UPDATE_BODY(f32_identity, f32_to_bf16)
-}
-
-PT_HOST_CLONES
-void host_update_fp16_g32(const HostConsts k, const float* __restrict__ g, float* __restrict__ w,
-                          float* __restrict__ m, float* __restrict__ v, uint16_t* __restrict__ p, uint64_t n) {
-  PT_HOST_UPDATE_BODY(f32_identity, f32_to_fp16)
-}
-
-PT_HOST_CLONES
-void host_update_fp16(const HostConsts k, const uint16_t* __restrict__ g, float* __restrict__ w,
-                      float* __restrict__ m, float* __restrict__ v, uint16_t* __restrict__ p, uint64_t n) {
-  PT_HOST_UPDATE_BODY(fp16_to_f32, f32_to_fp16)
-}
-
-constexpr uint64_t HOST_GRAIN = 1u << 18;   // elements one thread takes at a time
-
-}  // namespace
 
 extern "C" int pt_chunk_host_adamw_step(pt_ctx* ctx, const pt_hparams* hp, uint32_t first_chunk, uint32_t n_chunks,
                                         const void* const* h_grad, float* const* h_master, float* const* h_m,
@@ -134,60 +49,25 @@ extern "C" int pt_chunk_host_adamw_step(pt_ctx* ctx, const pt_hparams* hp, uint3
   PT_HIP(ctx, hipStreamSynchronize(ctx->s_scalar));
   const PtDevState& hs = *ctx->h_state;
   if (hs.skip) return PT_OK;                     // skipped step: the host arrays stay as they are
-  HostConsts k{hs.c[0], hs.c[1], hs.c[2], hs.c[3], hs.c[4], hs.c[5], hs.c[6], hs.c[7], hs.c[8]};
-
-  const uint64_t S = ctx->S;
-  const uint64_t grains_per_chunk = (S + HOST_GRAIN - 1) / HOST_GRAIN;
-  const uint64_t total_grains = grains_per_chunk * n_chunks;
-  std::atomic<uint64_t> next{0};
-  const int dtype = ctx->dtype;
-  const bool masked = !ctx->h_nd_begin.empty(), gf32 = ctx->grad_f32;
-  const uint32_t* nd_begin = ctx->h_nd_begin.data();
-  const uint64_t* nd_ranges = ctx->h_nd_ranges.data();
-  auto worker = [&]() {
-    for (;;) {
-      const uint64_t gidx = next.fetch_add(1, std::memory_order_relaxed);
-      if (gidx >= total_grains) return;
-      const uint64_t c = gidx / grains_per_chunk, lo = (gidx % grains_per_chunk) * HOST_GRAIN;
-      const uint64_t n = (lo + HOST_GRAIN <= S) ? HOST_GRAIN : S - lo;
-      const uint16_t* g = static_cast<const uint16_t*>(h_grad[c]) + lo;       // 16-bit gradient chunks
-      const float* g32 = static_cast<const float*>(h_grad[c]) + lo;          // fp32 gradient chunks
-      uint16_t* p = static_cast<uint16_t*>(h_param16[c]) + lo;
-      // runs of one decay factor: between and inside the chunk's no-decay ranges
-      uint64_t pos = lo;
-      const uint64_t end = lo + n;
-      uint32_t r = masked ? nd_begin[first_chunk + c] : 0;
-      const uint32_t r_end = masked ? nd_begin[first_chunk + c + 1] : 0;
-      while (r < r_end && nd_ranges[2 * size_t(r) + 1] <= pos) ++r;
-      while (pos < end) {
-        uint64_t stop = end;
-        HostConsts kk = k;
-        if (r < r_end && nd_ranges[2 * size_t(r)] < end) {
-          if (nd_ranges[2 * size_t(r)] > pos) stop = nd_ranges[2 * size_t(r)];          // decayed run up to the range
-          else { kk.decay = 1.0f; stop = std::min<uint64_t>(end, nd_ranges[2 * size_t(r) + 1]); ++r; }
-        }
-        const uint64_t off = pos - lo, cnt = stop - pos;
-        float* w_ = h_master[c] + pos; float* m_ = h_m[c] + pos; float* v_ = h_v[c] + pos;
-        if (gf32) {
-          if (dtype == PT_BF16) host_update_bf16_g32(kk, g32 + off, w_, m_, v_, p + off, cnt);
-          else host_update_fp16_g32(kk, g32 + off, w_, m_, v_, p + off, cnt);
-        } else {
-          if (dtype == PT_BF16) host_update_bf16(kk, g + off, w_, m_, v_, p + off, cnt);
-          else host_update_fp16(kk, g + off, w_, m_, v_, p + off, cnt);
-        }
-        pos = stop;
-      }
+  pt_host::Job job;
+  job.k = pt_host::Consts{hs.c[0], hs.c[1], hs.c[2], hs.c[3], hs.c[4], hs.c[5], hs.c[6], hs.c[7], hs.c[8]};
+  job.dtype_fp16 = ctx->dtype == PT_FP16;
+  job.grad_f32 = ctx->grad_f32;
+  job.S = ctx->S;
+  job.first_chunk = first_chunk;
+  job.n_chunks = n_chunks;
+  job.h_grad = h_grad; job.h_master = h_master; job.h_m = h_m; job.h_v = h_v; job.h_param16 = h_param16;
+  if (!ctx->h_nd_begin.empty()) { job.nd_begin = ctx->h_nd_begin.data(); job.nd_ranges = ctx->h_nd_ranges.data(); }
+  // The workers belong to the context and sleep between steps; they are (re)started only when the
+  // caller asks for another thread count.  This thread works along, so the pool holds n_threads - 1.
+  return pt_guarded(ctx, "pt_chunk_host_adamw_step", [&] {
+    if (!ctx->host_pool || ctx->host_pool_threads != n_threads) {
+      delete ctx->host_pool;
+      ctx->host_pool = nullptr;
+      ctx->host_pool = new pt_host::Pool(n_threads - 1);
+      ctx->host_pool_threads = n_threads;
     }
-  };
-  std::vector<std::thread> pool;
-  const uint32_t extra = n_threads - 1;
-  try {
-    pool.reserve(extra);
-    for (uint32_t t = 0; t < extra; ++t) pool.emplace_back(worker);
-  } catch (...) {
-    // could not start every thread: the shared work queue is drained by those that did start
-  }
-  worker();
-  for (auto& th : pool) th.join();
-  return PT_OK;
+    ctx->host_pool->run(job);
+    return int(PT_OK);
+  });
 }
