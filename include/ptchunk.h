@@ -138,6 +138,9 @@ int pt_ctx_set_no_decay(pt_ctx* ctx, const pt_segment* segs, uint32_t n_segs);
  *   "adamw_unroll"  4-element units a lane loads before it computes: 1, 2, 4 or 8
  *   "adamw_nt"      1 = non-temporal hints on the update's loads and stores (default), 0 = none
  *   "pack_tile_elems"  elements one workgroup of pack/unpack moves; read by pt_pack_plan_create
+ *   "stream_lanes"  copy streams per direction of the streamed path: 1 (default), or 2 - gradient +
+ *                   master on one upload stream and momentum + variance on another, likewise on the
+ *                   way back.  Choose before pt_stream_reserve (PT_ERR_STATE afterwards).
  * Gradient storage (variants of the path; the paper's gradients are the 16-bit array):
  *   "grad_fp32"     1 = the gradient chunks of this context hold fp32 (micro-batches accumulated
  *                   by pt_chunk_accum_grads): every `grad` / `h_grad` argument of the norm, the
@@ -236,7 +239,19 @@ int pt_chunk_unpack(pt_ctx* ctx, const pt_pack_plan* plan, const void* const* ch
  *   offloaded keeps its value).
  * finalize != 0: sums the per-chunk values of ALL chunks of the context in chunk
  *   order into sqnorm / norm / found_inf (device scalars) and opens the step for
- *   the update calls. */
+ *   the update calls.
+ *   PT_FINALIZE_STRICT (1): every chunk must have got its value in THIS step, i.e. since
+ *     the last pt_step_end, from a pack or accumulate plan that touches it or from a
+ *     recompute; otherwise PT_ERR_STATE - a chunk nobody reduced would enter the norm with
+ *     last step's sum and last step's non-finite flag.
+ *   PT_FINALIZE_CARRY (2): chunks without a value from this step keep their old one (a
+ *     gradient chunk that was reduced before it was offloaded and has not changed since).
+ *   A chunk keeps the value of the LAST call that reduced it: pack all of a chunk's
+ *   gradients with one plan per step (two plans that share a chunk leave the second
+ *   plan's partial only), or recompute the chunk afterwards.
+ *   PT_ERR_STATE while a streamed update is still open (pt_step_end closes it). */
+#define PT_FINALIZE_STRICT 1
+#define PT_FINALIZE_CARRY 2
 int pt_chunk_grad_sqnorm(pt_ctx* ctx, const void* const* grad_chunks, uint32_t first_chunk,
                          uint32_t n_chunks, int finalize, void* stream);
 
@@ -383,6 +398,15 @@ int pt_optim_choose(const pt_optim_rates* rates, uint64_t chunk_elems, uint32_t 
  * and size): the known-size kernel against which hardware traffic counters and the
  * attainable HBM rate of a box are calibrated.  Not part of the optimizer path. */
 int pt_calib_copy(void* dst, const void* src, uint64_t bytes, void* stream);
+
+/* The update's own memory access pattern with the arithmetic taken out: over chunks
+ * [first_chunk, first_chunk+n_chunks), with the pointers the last pt_chunk_adamw_step on them left in
+ * the context (PT_ERR_STATE if there was none) and the same launch shape, reads gradient, master,
+ * momentum and variance (14 bytes per element) and writes master, momentum and variance back as read and
+ * param16 re-derived from the master weight (14 bytes): the state keeps its values.  What it attains is
+ * the ceiling the memory system sets for this mix of four read and four write streams on this placement.
+ * 16-bit gradient chunks, no no-decay runs.  Not part of the optimizer path. */
+int pt_calib_adamw_pattern(pt_ctx* ctx, uint32_t first_chunk, uint32_t n_chunks, void* stream);
 
 #ifdef __cplusplus
 }

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libptchunk.so")
 
 PT_OK, PT_ERR_INVALID_ARG, PT_ERR_ALIGNMENT, PT_ERR_HIP, PT_ERR_STATE, PT_ERR_UNSUPPORTED, PT_ERR_NOMEM = range(7)
 PT_BF16, PT_FP16 = 0, 1
+PT_FINALIZE_STRICT, PT_FINALIZE_CARRY = 1, 2
 
 EXPORTS = [
     "pt_version", "pt_status_string", "pt_last_error", "pt_ctx_create", "pt_ctx_destroy", "pt_ctx_set_state",
@@ -23,7 +24,7 @@ EXPORTS = [
     "pt_step_report_read", "pt_update_consts_read", "pt_step_override", "pt_calib_copy", "pt_ctx_set_option",
     "pt_layout_grouped", "pt_chunk_size_search", "pt_chunk_host_adamw_step",
     "pt_optim_predict", "pt_optim_choose", "pt_ctx_set_no_decay", "pt_chunk_accum_grads",
-    "pt_chunk_grad_sqnorm_noalloc",
+    "pt_chunk_grad_sqnorm_noalloc", "pt_calib_adamw_pattern",
 ]
 
 
@@ -116,6 +117,7 @@ def lib():
         L.pt_update_consts_read.argtypes = [vp, C.POINTER(pt_update_consts), vp]
         L.pt_step_override.argtypes = [vp, C.c_float, i32, vp]
         L.pt_calib_copy.argtypes = [vp, vp, u64, vp]
+        L.pt_calib_adamw_pattern.argtypes = [vp, u32, u32, vp]
         L.pt_ctx_set_option.argtypes = [vp, C.c_char_p, C.c_int64]
         L.pt_ctx_set_no_decay.argtypes = [vp, C.POINTER(pt_segment), u32]
         dp = C.POINTER(C.c_double)
@@ -239,9 +241,10 @@ def pt_chunk_unpack(ctx, plan, chunks, stream=None):
     _check(lib().pt_chunk_unpack(ctx, plan, _ptr_array(chunks), _stream(stream)), "pt_chunk_unpack", ctx)
 
 
-def pt_chunk_grad_sqnorm(ctx, grad_chunks, first_chunk: int, n_chunks: int, finalize: bool, stream=None):
+def pt_chunk_grad_sqnorm(ctx, grad_chunks, first_chunk: int, n_chunks: int, finalize, stream=None):
+    """finalize: False / 0, True / PT_FINALIZE_STRICT, or PT_FINALIZE_CARRY"""
     _check(lib().pt_chunk_grad_sqnorm(ctx, _ptr_array(grad_chunks), int(first_chunk), int(n_chunks),
-                                      1 if finalize else 0, _stream(stream)), "pt_chunk_grad_sqnorm", ctx)
+                                      int(finalize), _stream(stream)), "pt_chunk_grad_sqnorm", ctx)
 
 
 def pt_chunk_grad_sqnorm_noalloc(grad_arena, dtype: int, chunk_elems: int, n_chunks: int, loss_scale: float,
@@ -294,6 +297,11 @@ def pt_step_override(ctx, grad_mult: float, found_inf: bool, stream=None):
 
 def pt_calib_copy(dst, src, nbytes: int, stream=None):
     _check(lib().pt_calib_copy(_addr(dst), _addr(src), int(nbytes), _stream(stream)), "pt_calib_copy")
+
+
+def pt_calib_adamw_pattern(ctx, first_chunk: int, n_chunks: int, stream=None):
+    _check(lib().pt_calib_adamw_pattern(ctx, int(first_chunk), int(n_chunks), _stream(stream)),
+           "pt_calib_adamw_pattern", ctx)
 
 
 def pt_ctx_set_option(ctx, name: str, value: int):

@@ -168,7 +168,10 @@ extern "C" int pt_chunk_accum_grads(pt_ctx* ctx, const pt_pack_plan* plan, float
   hipLaunchKernelGGL(kern, dim3(plan->n_tiles), dim3(AC_THREADS), 0, st, plan->d_tiles, pt_row(ctx, ROW_PACK),
                      ctx->d_state, plan->d_tile_sq, plan->d_tile_flag);
   PT_LAUNCH_CHECK(ctx, "k_accum");
-  if (take_norm)
-    return pt_launch_chunk_reduce(ctx, plan->d_tile_sq, plan->d_tile_flag, plan->d_chunk_tile_begin, 0, ctx->C, 0, st);
+  if (take_norm) {
+    rc = pt_launch_chunk_reduce(ctx, plan->d_tile_sq, plan->d_tile_flag, plan->d_chunk_tile_begin, 0, ctx->C, 0, st);
+    if (rc != PT_OK) return rc;
+    for (uint32_t c : plan->touched) ctx->chunk_fresh[c] = 1;
+  }
   return PT_OK;
 }

@@ -293,6 +293,56 @@ k_adamw(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_
   }
 }
 
+// Measurement aid: the update's memory access pattern with the arithmetic taken out.  Same tiles, same
+// block-to-tile mapping, the same four loads and four stores per unit with the same hints; master,
+// momentum and variance are stored back as loaded and param16 is re-derived from the master weight
+// (which is what it holds already), so the state does not change.  What this kernel attains is what the
+// memory system gives this mix of streams on this placement; the update itself cannot be faster.
+template <int DT, int UNROLL, bool NT>
+__global__ void __launch_bounds__(AW_THREADS)
+k_adamw_pattern(const uint64_t* __restrict__ table, uint32_t table_cols, uint32_t first_col, uint32_t n_cols,
+                uint64_t S, uint32_t tiles_per_chunk, uint32_t* __restrict__ sink) {
+  constexpr uint32_t TILE_UNITS = AW_THREADS * UNROLL;
+  const uint64_t units = S / 4;
+  const uint32_t total_tiles = tiles_per_chunk * n_cols;
+  uint32_t keep = 0;
+  for (uint32_t T = blockIdx.x; T < total_tiles; T += gridDim.x) {
+    const uint32_t ci = T / tiles_per_chunk, tile = T - ci * tiles_per_chunk;
+    const uint32_t col = first_col + ci;
+    cgu32x2_ptr gp = (cgu32x2_ptr)(table[size_t(ROW_GRAD) * table_cols + col]);
+    gf32x4_ptr wp = (gf32x4_ptr)(table[size_t(ROW_MASTER) * table_cols + col]);
+    gf32x4_ptr mp = (gf32x4_ptr)(table[size_t(ROW_M) * table_cols + col]);
+    gf32x4_ptr vp = (gf32x4_ptr)(table[size_t(ROW_V) * table_cols + col]);
+    gu32x2_ptr pp = (gu32x2_ptr)(table[size_t(ROW_P16) * table_cols + col]);
+    const uint64_t u0 = uint64_t(tile) * TILE_UNITS + threadIdx.x;
+    if ((uint64_t(tile) + 1) * TILE_UNITS > units) continue;      // ragged last tiles are left out (a few KiB per chunk)
+    u32x2 g[UNROLL]; f32x4 w[UNROLL], m[UNROLL], v[UNROLL];
+#pragma unroll
+    for (int r = 0; r < UNROLL; ++r) {
+      const uint64_t u = u0 + uint64_t(r) * AW_THREADS;
+      g[r] = ld_stream<NT>(gp + u);
+      w[r] = ld_stream<NT>(wp + u);
+      m[r] = ld_stream<NT>(mp + u);
+      v[r] = ld_stream<NT>(vp + u);
+    }
+#pragma unroll
+    for (int r = 0; r < UNROLL; ++r) {
+      const uint64_t u = u0 + uint64_t(r) * AW_THREADS;
+      // opaque to the optimiser, so that the stores of unchanged values are not dropped
+      asm volatile("" : "+v"(w[r]), "+v"(m[r]), "+v"(v[r]));
+      u32x2 p;
+      p.x = encode16<DT>(w[r][0]) | (encode16<DT>(w[r][1]) << 16);
+      p.y = encode16<DT>(w[r][2]) | (encode16<DT>(w[r][3]) << 16);
+      keep ^= g[r].x ^ g[r].y;
+      st_stream<NT>(w[r], wp + u);
+      st_stream<NT>(m[r], mp + u);
+      st_stream<NT>(v[r], vp + u);
+      st_stream<NT>(p, pp + u);
+    }
+  }
+  if (keep == 0x9e3779b9u && sink) *sink = keep;      // keeps the gradient loads alive; practically never taken
+}
+
 typedef void (*adamw_kernel_t)(const uint64_t*, uint32_t, uint32_t, uint32_t, uint64_t, uint32_t,
                                const PtDevState*, int, const uint32_t*, const uint64_t*, uint32_t, int);
 
@@ -375,4 +425,45 @@ extern "C" int pt_chunk_adamw_step(pt_ctx* ctx, const pt_hparams* hp, uint32_t f
   if ((rc = pt_table_bind(ctx, ROW_P16, first_chunk, n_chunks, (const void* const*)param16, false, st, nullptr)) != PT_OK) return rc;
   if ((rc = pt_prepare_consts(ctx, hp, st)) != PT_OK) return rc;
   return pt_launch_adamw(ctx, first_chunk, n_chunks, st, false, first_chunk, ctx->opt_zero_grads != 0);
+}
+
+extern "C" int pt_calib_adamw_pattern(pt_ctx* ctx, uint32_t first_chunk, uint32_t n_chunks, void* stream) {
+  if (!ctx) return PT_ERR_INVALID_ARG;
+  if (uint64_t(first_chunk) + n_chunks > ctx->C)
+    return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_calib_adamw_pattern: chunks [%u, %u) outside the context's %u chunks",
+                   first_chunk, first_chunk + n_chunks, ctx->C);
+  if (ctx->grad_f32 || ctx->d_nd_begin)
+    return pt_fail(ctx, PT_ERR_UNSUPPORTED, "pt_calib_adamw_pattern: 16-bit gradient chunks without no-decay runs only");
+  const uint64_t* h = ctx->h_table.data();
+  for (uint32_t c = first_chunk; c < first_chunk + n_chunks; ++c)
+    for (int row : {ROW_GRAD, ROW_MASTER, ROW_M, ROW_V, ROW_P16})
+      if (!h[size_t(row) * ctx->table_cols + c])
+        return pt_fail(ctx, PT_ERR_STATE, "pt_calib_adamw_pattern: chunk %u has not been through pt_chunk_adamw_step yet "
+                       "(its pointers are not in the context's table)", c);
+  if (n_chunks == 0) return PT_OK;
+  const uint32_t unroll = ctx->opt_adamw_unroll;
+  const uint64_t units = ctx->S / 4, tile_units = uint64_t(AW_THREADS) * unroll;
+  const uint64_t tpc = (units + tile_units - 1) / tile_units;
+  if (tpc * n_chunks > 0x7fffffffull) return pt_fail(ctx, PT_ERR_UNSUPPORTED, "pt_calib_adamw_pattern: more than 2^31 tiles");
+  const uint32_t total = uint32_t(tpc) * n_chunks;
+  uint32_t want = ctx->opt_adamw_grid > 0 ? ctx->opt_adamw_grid : (total + 2) / 3;      // as pt_launch_adamw
+  if (ctx->opt_adamw_grid == 0 && want < PT_ADAMW_MIN_GRID) want = PT_ADAMW_MIN_GRID;
+  dim3 grid(want < total ? want : total);
+  typedef void (*pattern_kernel_t)(const uint64_t*, uint32_t, uint32_t, uint32_t, uint64_t, uint32_t, uint32_t*);
+  const bool bf = ctx->dtype == PT_BF16, nt = ctx->opt_adamw_nt != 0;
+  pattern_kernel_t kern;
+  switch (unroll) {
+    case 1: kern = bf ? (nt ? k_adamw_pattern<PT_BF16, 1, true> : k_adamw_pattern<PT_BF16, 1, false>)
+                      : (nt ? k_adamw_pattern<PT_FP16, 1, true> : k_adamw_pattern<PT_FP16, 1, false>); break;
+    case 2: kern = bf ? (nt ? k_adamw_pattern<PT_BF16, 2, true> : k_adamw_pattern<PT_BF16, 2, false>)
+                      : (nt ? k_adamw_pattern<PT_FP16, 2, true> : k_adamw_pattern<PT_FP16, 2, false>); break;
+    case 8: kern = bf ? (nt ? k_adamw_pattern<PT_BF16, 8, true> : k_adamw_pattern<PT_BF16, 8, false>)
+                      : (nt ? k_adamw_pattern<PT_FP16, 8, true> : k_adamw_pattern<PT_FP16, 8, false>); break;
+    default: kern = bf ? (nt ? k_adamw_pattern<PT_BF16, 4, true> : k_adamw_pattern<PT_BF16, 4, false>)
+                       : (nt ? k_adamw_pattern<PT_FP16, 4, true> : k_adamw_pattern<PT_FP16, 4, false>); break;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(AW_THREADS), 0, (hipStream_t)stream, ctx->d_table, ctx->table_cols, first_chunk,
+                     n_chunks, ctx->S, uint32_t(tpc), (uint32_t*)nullptr);
+  PT_LAUNCH_CHECK(ctx, "k_adamw_pattern");
+  return PT_OK;
 }

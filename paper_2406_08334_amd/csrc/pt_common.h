@@ -55,6 +55,7 @@ enum PtRow : int {
 };
 
 constexpr uint32_t PT_MAX_SLOTS = 8;
+constexpr uint32_t PT_MAX_LANES = 2;           // copy streams per direction of the streamed path
 constexpr uint32_t PT_ADAMW_MIN_GRID = 16384;      // default grid of the update kernel: max(this, tiles / 3)
 constexpr uint32_t PT_ADAMW_DEFAULT_UNROLL = 4;
 constexpr uint32_t PT_NORM_BLOCK_ELEMS = 32768;  // elements one block of the norm kernel reduces
@@ -105,6 +106,7 @@ struct pt_ctx {
   uint32_t* d_norm_flag = nullptr;      // [C * norm_blocks]
 
   // host-side step bookkeeping
+  std::vector<uint8_t> chunk_fresh;     // [C] 1 = the chunk's sum of squares was taken in this step (since pt_step_end)
   bool norm_finalized = false;
   bool prepared = false;
   pt_hparams prepared_hp{};
@@ -112,9 +114,12 @@ struct pt_ctx {
   // streamed path
   uint32_t n_slots = 0;
   void* slot_mem[PT_MAX_SLOTS] = {};
-  hipStream_t s_up = nullptr, s_comp = nullptr, s_down = nullptr;
+  // A chunk's four arrays travel on `stream_lanes` upload streams and as many offload streams
+  // (lane 0: gradient + master up, master + param16 down; lane 1: momentum + variance both ways).
+  uint32_t stream_lanes = 1;            // option "stream_lanes": 1 or 2, chosen before pt_stream_reserve
+  hipStream_t s_up[PT_MAX_LANES] = {}, s_comp = nullptr, s_down[PT_MAX_LANES] = {};
   hipEvent_t ev_fork = nullptr;
-  hipEvent_t ev_up[PT_MAX_SLOTS] = {}, ev_k[PT_MAX_SLOTS] = {}, ev_down[PT_MAX_SLOTS] = {};
+  hipEvent_t ev_up[PT_MAX_LANES][PT_MAX_SLOTS] = {}, ev_k[PT_MAX_SLOTS] = {}, ev_down[PT_MAX_LANES][PT_MAX_SLOTS] = {};
   bool slot_used[PT_MAX_SLOTS] = {};
   bool stream_pending = false;
   uint32_t last_slot = 0;
@@ -214,6 +219,10 @@ int pt_prepare_consts(pt_ctx* ctx, const pt_hparams* hp, hipStream_t stream);
 // zero_grads: overwrite the gradient chunks with zeros once read (resident chunks only).
 int pt_launch_adamw(pt_ctx* ctx, uint32_t first_col, uint32_t n_cols, hipStream_t stream, bool recast_on_skip,
                     uint32_t mask_chunk0, bool zero_grads);
+
+// ---- implemented in pt_stream.hip ----------------------------------------------------------
+// Destroys the streamed path's streams and events and frees its chunk buffers (no-op when none).
+void pt_stream_release(pt_ctx* ctx);
 
 // ---- implemented in pt_host.hip ------------------------------------------------------------
 // Stops and joins the context's worker threads (no-op when there are none).

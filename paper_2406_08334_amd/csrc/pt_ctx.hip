@@ -93,16 +93,7 @@ extern "C" const char* pt_last_error(const pt_ctx* ctx) {
 
 static void ctx_free_all(pt_ctx* ctx) {
   pt_host_pool_destroy(ctx);
-  if (ctx->s_up) (void)hipStreamDestroy(ctx->s_up);
-  if (ctx->s_comp) (void)hipStreamDestroy(ctx->s_comp);
-  if (ctx->s_down) (void)hipStreamDestroy(ctx->s_down);
-  if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
-  for (uint32_t s = 0; s < PT_MAX_SLOTS; ++s) {
-    if (ctx->ev_up[s]) (void)hipEventDestroy(ctx->ev_up[s]);
-    if (ctx->ev_k[s]) (void)hipEventDestroy(ctx->ev_k[s]);
-    if (ctx->ev_down[s]) (void)hipEventDestroy(ctx->ev_down[s]);
-    if (ctx->slot_mem[s]) (void)hipFree(ctx->slot_mem[s]);
-  }
+  pt_stream_release(ctx);
   if (ctx->s_scalar) (void)hipStreamDestroy(ctx->s_scalar);
   if (ctx->ev_scalar) (void)hipEventDestroy(ctx->ev_scalar);
   if (ctx->h_state) (void)hipHostFree(ctx->h_state);
@@ -124,6 +115,7 @@ static int ctx_alloc(pt_ctx* ctx, const pt_scaler_cfg* sc) {
   PT_HIP(ctx, hipMalloc(&ctx->d_table, tab_bytes));
   PT_HIP(ctx, hipMemset(ctx->d_table, 0, tab_bytes));
   ctx->h_table.assign(size_t(N_ROWS) * ctx->table_cols, 0);
+  ctx->chunk_fresh.assign(ctx->C, 0);
   PT_HIP(ctx, hipMalloc(&ctx->d_chunk_sq, ctx->C * sizeof(double)));
   PT_HIP(ctx, hipMemset(ctx->d_chunk_sq, 0, ctx->C * sizeof(double)));
   PT_HIP(ctx, hipMalloc(&ctx->d_chunk_flag, ctx->C * sizeof(uint32_t)));
@@ -225,6 +217,13 @@ extern "C" int pt_ctx_set_option(pt_ctx* ctx, const char* name, int64_t value) {
     ctx->opt_adamw_nt = value != 0;
     return PT_OK;
   }
+  if (std::strcmp(name, "stream_lanes") == 0) {
+    if (value < 1 || value > int64_t(PT_MAX_LANES)) return pt_fail(ctx, PT_ERR_INVALID_ARG, "stream_lanes must be 1 or 2");
+    if (ctx->n_slots && uint32_t(value) != ctx->stream_lanes)
+      return pt_fail(ctx, PT_ERR_STATE, "stream_lanes must be chosen before pt_stream_reserve (it creates the copy streams)");
+    ctx->stream_lanes = uint32_t(value);
+    return PT_OK;
+  }
   if (std::strcmp(name, "adamw_zero_grads") == 0) {
     ctx->opt_zero_grads = value != 0;
     return PT_OK;
@@ -290,6 +289,9 @@ static int set_no_decay(pt_ctx* ctx, const pt_segment* segs, uint32_t n_segs) {
 
 extern "C" int pt_step_override(pt_ctx* ctx, float grad_mult, int32_t found_inf, void* stream) {
   if (!ctx) return PT_ERR_INVALID_ARG;
+  if (ctx->stream_pending)
+    return pt_fail(ctx, PT_ERR_STATE, "pt_step_override: a streamed update is still open (its kernels read the step's "
+                   "scalars); close the step with pt_step_end first");
   hipLaunchKernelGGL(k_override, dim3(1), dim3(1), 0, (hipStream_t)stream, ctx->d_state, grad_mult,
                      found_inf ? 1 : 0);
   PT_LAUNCH_CHECK(ctx, "k_override");
@@ -302,14 +304,16 @@ extern "C" int pt_step_end(pt_ctx* ctx, void* stream) {
   if (!ctx) return PT_ERR_INVALID_ARG;
   hipStream_t st = (hipStream_t)stream;
   if (ctx->stream_pending) {
-    // offloads complete in order on one stream: the last one recorded covers them all
-    PT_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_down[ctx->last_slot], 0));
+    // offloads complete in order on each offload stream: the last event recorded on it covers them all
+    for (uint32_t l = 0; l < ctx->stream_lanes; ++l)
+      PT_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_down[l][ctx->last_slot], 0));
     ctx->stream_pending = false;
   }
   hipLaunchKernelGGL(k_step_end, dim3(1), dim3(1), 0, st, ctx->d_state);
   PT_LAUNCH_CHECK(ctx, "k_step_end");
   ctx->norm_finalized = false;
   ctx->prepared = false;
+  std::fill(ctx->chunk_fresh.begin(), ctx->chunk_fresh.end(), uint8_t(0));   // the next step needs new partial sums
   return PT_OK;
 }
 
@@ -347,11 +351,13 @@ int pt_table_bind(pt_ctx* ctx, int row, uint32_t first, uint32_t n, const void* 
     if (h[i] != p) diff = true;
   }
   if (diff) {
-    for (uint32_t i = 0; i < n; ++i) h[i] = (uint64_t)(uintptr_t)ptrs[i];
-    // Work already enqueued may still read the old entries: drain it first.
+    // Work already enqueued may still read the old entries: drain it first.  The host shadow takes
+    // the new pointers only once the device table holds them, so a failed upload is retried by the
+    // next call instead of being taken for done.
     PT_HIP(ctx, hipStreamSynchronize(stream));
-    PT_HIP(ctx, hipMemcpy(ctx->d_table + size_t(row) * ctx->table_cols + first, h, n * sizeof(uint64_t),
+    PT_HIP(ctx, hipMemcpy(ctx->d_table + size_t(row) * ctx->table_cols + first, ptrs, n * sizeof(uint64_t),
                           hipMemcpyHostToDevice));
+    for (uint32_t i = 0; i < n; ++i) h[i] = (uint64_t)(uintptr_t)ptrs[i];
   }
   if (changed) *changed = diff;
   return PT_OK;

@@ -205,6 +205,8 @@ extern "C" int pt_chunk_grad_sqnorm(pt_ctx* ctx, const void* const* grad_chunks,
   if (uint64_t(first_chunk) + n_chunks > ctx->C)
     return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_chunk_grad_sqnorm: chunks [%u, %u) outside the context's %u chunks",
                    first_chunk, first_chunk + n_chunks, ctx->C);
+  if (finalize < 0 || finalize > PT_FINALIZE_CARRY)
+    return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_chunk_grad_sqnorm: finalize must be 0, PT_FINALIZE_STRICT or PT_FINALIZE_CARRY");
   if (grad_chunks && n_chunks) {
     int rc = pt_table_bind(ctx, ROW_PACK, first_chunk, n_chunks, grad_chunks + first_chunk, false, st, nullptr);
     if (rc != PT_OK) return rc;
@@ -222,8 +224,19 @@ extern "C" int pt_chunk_grad_sqnorm(pt_ctx* ctx, const void* const* grad_chunks,
     int rc2 = pt_launch_chunk_reduce(ctx, ctx->d_norm_part, ctx->d_norm_flag, nullptr, first_chunk, n_chunks,
                                      ctx->norm_blocks, st);
     if (rc2 != PT_OK) return rc2;
+    for (uint32_t c = first_chunk; c < first_chunk + n_chunks; ++c) ctx->chunk_fresh[c] = 1;
   }
   if (finalize) {
+    if (ctx->stream_pending)
+      return pt_fail(ctx, PT_ERR_STATE, "pt_chunk_grad_sqnorm: a streamed update is still open (its kernels read the "
+                     "step's scalars); close the step with pt_step_end first");
+    if (finalize != PT_FINALIZE_CARRY) {
+      for (uint32_t c = 0; c < ctx->C; ++c)
+        if (!ctx->chunk_fresh[c])
+          return pt_fail(ctx, PT_ERR_STATE, "pt_chunk_grad_sqnorm: chunk %u has no sum of squares from this step (nothing "
+                         "packed, accumulated or recomputed for it since the last pt_step_end); its old value would enter "
+                         "the norm - finalize with PT_FINALIZE_CARRY if that is meant", c);
+    }
     hipLaunchKernelGGL(k_finalize, dim3(1), dim3(64), 0, st, ctx->d_chunk_sq, ctx->d_chunk_flag, ctx->C,
                        ctx->d_state);
     PT_LAUNCH_CHECK(ctx, "k_finalize");

@@ -274,8 +274,11 @@ static int run_pack(pt_ctx* ctx, const pt_pack_plan* plan, const void* const* ch
     hipLaunchKernelGGL((k_pack<PT_FP16, DIR>), grid, dim3(PK_THREADS), lds, st, plan->d_tiles, pt_row(ctx, row),
                        ctx->d_state, plan->d_tile_sq, plan->d_tile_flag);
   PT_LAUNCH_CHECK(ctx, who);
-  if (DIR == 0)
-    return pt_launch_chunk_reduce(ctx, plan->d_tile_sq, plan->d_tile_flag, plan->d_chunk_tile_begin, 0, ctx->C, 0, st);
+  if (DIR == 0) {
+    rc = pt_launch_chunk_reduce(ctx, plan->d_tile_sq, plan->d_tile_flag, plan->d_chunk_tile_begin, 0, ctx->C, 0, st);
+    if (rc != PT_OK) return rc;
+    for (uint32_t c : plan->touched) ctx->chunk_fresh[c] = 1;
+  }
   return PT_OK;
 }
 

@@ -100,7 +100,8 @@ int main(int argc, char** argv) {
     CHECK_HIP(hipEventRecord(e[0], st));
     CHECK_PT(ctx, pt_chunk_pack_grads(ctx, plan, g.data(), st));
     CHECK_HIP(hipEventRecord(e[1], st));
-    CHECK_PT(ctx, pt_chunk_grad_sqnorm(ctx, nullptr, 0, C, 1, st));
+    // host chunks (if any) were never reduced in this driver: their sums stay at their initial zero
+    CHECK_PT(ctx, pt_chunk_grad_sqnorm(ctx, nullptr, 0, C, n_host ? PT_FINALIZE_CARRY : PT_FINALIZE_STRICT, st));
     CHECK_HIP(hipEventRecord(e[2], st));
     CHECK_PT(ctx, pt_chunk_adamw_step(ctx, &hpar, 0, C, g.data(), w.data(), m.data(), v.data(), p.data(), st));
     CHECK_HIP(hipEventRecord(e[3], st));
@@ -135,7 +136,7 @@ int main(int argc, char** argv) {
     for (int s = 0; s < steps; ++s) {
       CHECK_HIP(hipEventRecord(e[0], st));
       CHECK_PT(ctx, pt_chunk_pack_grads(ctx, plan, g.data(), st));
-      CHECK_PT(ctx, pt_chunk_grad_sqnorm(ctx, nullptr, 0, C, 1, st));
+      CHECK_PT(ctx, pt_chunk_grad_sqnorm(ctx, nullptr, 0, C, PT_FINALIZE_CARRY, st));
       CHECK_PT(ctx, pt_chunk_stream_step(ctx, &hpar, C, n_host, hgp.data(), hwp.data(), hmp.data(), hvp.data(), hpp.data(), st));
       CHECK_PT(ctx, pt_chunk_adamw_step(ctx, &hpar, 0, C, g.data(), w.data(), m.data(), v.data(), p.data(), st));
       CHECK_PT(ctx, pt_step_end(ctx, st));
