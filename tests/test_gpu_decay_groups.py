@@ -102,16 +102,16 @@ def test_end_to_end_gpt2_block_with_biases_and_norm_gains_undecayed(orc):
 
 @pytest.mark.parametrize("dtype,scaler", [(torch.bfloat16, None),
                                           (torch.float16, B.pt_scaler_cfg(65536.0, 2.0, 0.5, 2000, 0))])
-def test_streamed_and_host_updated_chunks_honour_the_runs(dtype, scaler):
+def test_streamed_and_host_updated_chunks_honour_the_runs(orc, dtype, scaler):
     S = 40_000
     sizes = [6 * S - 24]
     runs = [(0, 0, 100), (1, 39_000, 1000), (2, 0, S), (3, 4095, 3), (3, 20_000, 9000), (5, 39_900, 76)]
-    ref = run_mixed(sizes, S, 6, 2, steps=2, dtype=dtype, scaler=scaler, no_decay_runs=runs)
+    ref = run_mixed(sizes, S, 6, 2, steps=2, dtype=dtype, scaler=scaler, no_decay_runs=runs, orc=orc)
     plain = run_mixed(sizes, S, 6, 2, steps=2, dtype=dtype, scaler=scaler)
     assert not torch.equal(ref["w"], plain["w"])
     for n_persist, n_slots, host_update in ((3, 2, False), (0, 3, False), (5, 2, False), (3, 2, True), (0, 2, True)):
         got = run_mixed(sizes, S, n_persist, n_slots, steps=2, dtype=dtype, scaler=scaler, host_update=host_update,
-                        no_decay_runs=runs)
+                        no_decay_runs=runs, orc=orc)     # every chunk, wherever it is updated, against the oracle
         for name in ("p16", "w", "m", "v"):
             view = torch.int16 if got[name].element_size() == 2 else torch.int32
             assert torch.equal(got[name].view(view), ref[name].view(view)), (name, n_persist, n_slots, host_update)

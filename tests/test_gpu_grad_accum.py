@@ -12,7 +12,7 @@ from paper_2406_08334_amd import shapes
 
 from gpu_harness import ChunkedState, hp_pair, to_u16, same_bits, assert_same_bits
 from test_gpu_parity import RAGGED, ALIGNED
-from tolerance import ScaleTracker, check_p16
+from tolerance import ScaleTracker, check_p16, far_cap
 
 pytestmark = pytest.mark.gpu
 
@@ -136,12 +136,12 @@ def test_update_from_fp32_gradients_is_bit_exact_against_the_f32_sequence(orc, d
             trk.check((got["w"], got["m"], got["v"]), (h64["w"], h64["m"], h64["v"]), tol=1e-6)
             far = check_p16(orc.decode16(got["p16"], st.orc_dtype), orc.decode16(h64["p16"], st.orc_dtype), h64["w"],
                             trk.W, dtype == torch.float16)
-            assert far <= 1e-4 * got["p16"].size
+            assert far <= far_cap(got["p16"].size)
     finally:
         st.close()
 
 
-def test_zeroing_also_serves_16_bit_gradient_chunks_and_spares_a_skipped_step(orc):
+def test_zeroing_also_serves_16_bit_gradient_chunks_and_clears_a_skipped_step(orc):
     S = 4096 * 2 + 8
     st = ChunkedState([3 * S - 3], S, dtype=torch.float16, scaler=SCALER_B)
     try:
@@ -154,18 +154,57 @@ def test_zeroing_also_serves_16_bit_gradient_chunks_and_spares_a_skipped_step(or
                 if bad:
                     s_.grad_src.view(torch.int16)[77] = 0x7C00
                 s_.pack(); s_.norm()
-            before = to_u16(st.g16).copy()
             st.adamw(hp_b); ref.adamw(hp_b)
             st.end(); ref.end()
             a, b = st.host_state(), ref.host_state()
             for name in ("w", "m", "v", "p16"):
                 assert same_bits(a[name], b[name]), (name, step)     # zeroing changes no result
-            if bad:
-                assert same_bits(to_u16(st.g16), before)              # skipped: gradients stay
-            else:
-                assert not a["g16"].any()
+            assert not a["g16"].any()                                  # zeroed after an applied AND after a skipped step
         assert st.report().step == 2
         ref.close()
+    finally:
+        st.close()
+
+
+def test_add_into_accumulation_recovers_after_an_overflow(orc):
+    """A caller whose backward pass ADDS into the fp32 gradient chunks (no overwrite for the first
+    micro-batch) relies on the update to zero them.  With an inf in step 2 the step is skipped, the
+    loss scale halves, and step 3 must be applied again: the inf may not stay in the sums."""
+    S = 4096 + 8
+    sizes = [2 * S - 5]
+    st = ChunkedState(sizes, S, dtype=torch.float16, scaler=SCALER_B, grad_fp32=True)
+    try:
+        B.pt_ctx_set_option(st.ctx, "adamw_zero_grads", 1)
+        hp_b, hp_o, _ = hp_pair()
+        host = st.host_state()
+        SCALER_O = orc.ScalerCfg(65536.0, 2.0, 0.5, 2000, 1)
+        ost = orc.new_state(SCALER_O)
+        n = st.C * S
+        found = []
+        for step, bad in ((1, False), (2, True), (3, False), (4, False)):
+            sigma = ost.loss_scale
+            g32 = np.zeros(n, np.float32)
+            for micro in range(2):
+                st.set_grads(step, scale=sigma, micro=micro)
+                if bad and micro == 0:
+                    st.grad_src.view(torch.int16)[31] = 0x7C00
+                st.accum(overwrite=False, take_norm=(micro == 1))      # always adds: the chunks start at zero
+                src = to_u16(st.grad_src[:st.N])
+                part = np.zeros(n, np.uint16); part[:st.N] = src
+                orc.accum_f32(part, g32, st.orc_dtype, overwrite=False)
+            st.norm()
+            st.adamw(hp_b)
+            rep = st.report()
+            st.end()
+            found.append(rep.found_inf)
+            orep = orc.step_g32(hp_o, SCALER_O, ost, g32, host["w"], host["m"], host["v"], host["p16"], S, st.orc_dtype,
+                                use_f32seq=True, threads=4)
+            assert rep.found_inf == orep.found_inf == int(bad)
+            got = st.host_state()
+            for name in ("w", "m", "v", "p16"):
+                assert_same_bits(got[name], host[name], (name, step))
+            assert not got["g32"].view(np.uint32).any(), step
+        assert found == [0, 1, 0, 0] and st.report().step == 3 and st.report().loss_scale == 32768.0
     finally:
         st.close()
 
@@ -216,7 +255,7 @@ def end_to_end_accum(orc, sizes, S, dtype, steps, micro, scaler_b=None, scaler_o
             trk.check((got["w"], got["m"], got["v"]), (host["w"], host["m"], host["v"]), tol=1e-6)
             far = check_p16(orc.decode16(got["p16"], st.orc_dtype), orc.decode16(host["p16"], st.orc_dtype),
                             host["w"], trk.W, dtype == torch.float16)
-            assert far <= 1e-4 * got["p16"].size
+            assert far <= far_cap(got["p16"].size)
             consts = orc.consts_f32(hp_o, ost.t, orep.grad_mult)            # the oracle's own constants
             assert same_bits(np.array(list(k_.c), dtype=np.float32), consts)
             orc.adamw_f32seq_g32(consts, g32, fa["w"], fa["m"], fa["v"], fa["p16"], st.orc_dtype, threads=8, no_decay=mask)
@@ -243,17 +282,26 @@ def test_end_to_end_fp16_loss_scaling_with_an_inf_in_the_middle_micro_batch(orc)
     assert [r.loss_scale for r, _ in reps] == [65536.0, 65536.0, 32768.0, 32768.0]
 
 
-def run_split(n_persist, mode, dtype, scaler, steps=2, micro=2, masked=True):
+def run_split(n_persist, mode, dtype, scaler, steps=2, micro=2, masked=True, orc=None):
     """6 chunks with fp32 gradient chunks; chunks >= n_persist live in pinned host memory and are
-    streamed through chunk buffers (mode 'stream') or updated by host threads (mode 'host')."""
+    streamed through chunk buffers (mode 'stream') or updated by host threads (mode 'host').  With
+    `orc` the oracle accumulates the same seeded micro-batches and takes every step itself; all
+    chunks must end up with its bits."""
     S = 40_000
     st = ChunkedState([6 * S - 24], S, dtype=dtype, scaler=scaler, grad_fp32=True)
     try:
-        hp_b, _, _ = hp_pair()
+        hp_b, hp_o, _ = hp_pair()
+        mask = None
         if masked:
-            st.set_no_decay(runs=[(0, 0, 100), (2, 0, S), (3, 4095, 3), (5, 39_900, 76)])
+            mask = st.set_no_decay(runs=[(0, 0, 100), (2, 0, S), (3, 4095, 3), (5, 39_900, 76)])
         C = st.C
         host = {}
+        if orc is not None:
+            shadow = st.host_state()
+            sc_o = None if scaler is None else orc.ScalerCfg(scaler.init_scale, scaler.growth, scaler.backoff,
+                                                             scaler.growth_interval, 1)
+            ost = orc.new_state(sc_o)
+            og32 = np.zeros(C * S, np.float32)
         if n_persist < C:
             if mode == "stream":
                 B.pt_stream_reserve(st.ctx, 3)
@@ -268,6 +316,11 @@ def run_split(n_persist, mode, dtype, scaler, steps=2, micro=2, masked=True):
             for k in range(micro):
                 st.set_grads(s, scale=sigma, micro=k)
                 st.accum(overwrite=(k == 0), take_norm=(k == micro - 1))
+                if orc is not None:
+                    orc.accum_f32(st.oracle_packed(orc), og32, st.orc_dtype, overwrite=(k == 0))
+            if orc is not None:
+                orc.step_g32(hp_o, sc_o, ost, og32, shadow["w"], shadow["m"], shadow["v"], shadow["p16"], S, st.orc_dtype,
+                             use_f32seq=True, threads=4, no_decay=mask)
             for i, c in enumerate(range(n_persist, C)):
                 host["g32"][i].copy_(st.g32[c])
             torch.cuda.synchronize()
@@ -288,16 +341,20 @@ def run_split(n_persist, mode, dtype, scaler, steps=2, micro=2, masked=True):
             for i, c in enumerate(range(n_persist, C)):
                 full[c].copy_(host[name][i])
             out[name] = full.cpu()
+        if orc is not None:
+            for name in ("p16", "w", "m", "v"):
+                got = to_u16(out[name]).reshape(-1) if out[name].element_size() == 2 else out[name].numpy().reshape(-1)
+                assert_same_bits(got, shadow[name], (name, "against the oracle", n_persist, mode))
         return out
     finally:
         st.close()
 
 
 @pytest.mark.parametrize("dtype,scaler", [(torch.bfloat16, None), (torch.float16, SCALER_B)])
-def test_streamed_and_host_updated_chunks_with_fp32_gradients_give_the_resident_bits(dtype, scaler):
-    ref = run_split(6, "stream", dtype, scaler)
+def test_streamed_and_host_updated_chunks_with_fp32_gradients_equal_the_oracle_and_the_resident_bits(orc, dtype, scaler):
+    ref = run_split(6, "stream", dtype, scaler, orc=orc)
     for n_persist, mode in ((3, "stream"), (0, "stream"), (5, "stream"), (3, "host"), (0, "host")):
-        got = run_split(n_persist, mode, dtype, scaler)
+        got = run_split(n_persist, mode, dtype, scaler, orc=orc)
         for name in ("p16", "w", "m", "v"):
             view = torch.int16 if got[name].element_size() == 2 else torch.int32
             assert torch.equal(got[name].view(view), ref[name].view(view)), (name, n_persist, mode)
