@@ -14,7 +14,7 @@ in fp16 with dynamic loss scaling, and the LLaMA-13B shape with half of the chun
 host memory (streamed through chunk buffers, and updated by host threads).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama_7b] [--headline-only]
-    python bench.py --stream [--host-update] [--model] [--lanes 2]     # the split configuration alone
+    python bench.py --stream [--host-update] [--model]                 # the split configuration alone
 """
 from __future__ import annotations
 
@@ -22,6 +22,7 @@ import argparse
 import gc
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -384,7 +385,7 @@ def cpu_oracle_legs(cpu_in, S, n_threads_chunks, n_one_thread_chunks):
 
 # ---------------------------------------------------------------- half of the chunks in pinned host memory
 
-def run_split(steps, warmup, slots=3, lanes=1, host_chunks=0, host_update=False, host_threads=0, model=False):
+def run_split(steps, warmup, slots=3, host_chunks=0, host_update=False, host_threads=0, model=False):
     """LLaMA-13B-shaped state: chunks [0, C/2) resident in HBM, chunks [C/2, C/2 + n_host) in pinned host memory
     (as many of the configuration's 97 as the box lets the process pin).  Timed step = pack (resident) -> finalize ->
     pt_chunk_stream_step (host chunks, side streams) -> pt_chunk_adamw_step (resident, overlapped) -> pt_step_end
@@ -406,10 +407,9 @@ def run_split(steps, warmup, slots=3, lanes=1, host_chunks=0, host_update=False,
     n_host = n_want
     log(f"[bench] llama_13b: {C} chunks of {S:,}; {n_persist} resident ({16 * n_persist * S / 1e9:.1f} GB HBM), "
         f"{n_host} wanted in pinned host memory ({16 * n_host * S / 1e9:.1f} GB; host RAM {host_memory_gb()} GB), "
-        f"{slots} chunk buffers, {lanes} copy stream(s) per direction")
+        f"{slots} chunk buffers")
     t0 = time.time()
     ctx = B.pt_ctx_create(B.PT_BF16, S, C, None)
-    B.pt_ctx_set_option(ctx, "stream_lanes", lanes)
     B.pt_stream_reserve(ctx, slots)
     n_res = n_persist * S
     g16, p16, w, m, v = spread_arenas(
@@ -557,8 +557,8 @@ def run_split(steps, warmup, slots=3, lanes=1, host_chunks=0, host_update=False,
         "workload": f"llama_13b: {C} chunks of {S}; chunks [0,{n_persist}) resident, [{n_persist},{n_persist + n_host}) in pinned "
                     f"host memory ({n_host} of the configuration's {C - n_persist}: the box pins at most "
                     f"{pin_limit_gb if pin_limit_gb else '>= ' + str(round(16 * n_host * S / 1e9, 1))} GB of its {host_memory_gb()} GB RAM), "
-                    f"{slots} chunk buffers, {lanes} copy stream(s) per direction",
-        "n_persist": n_persist, "n_host": n_host, "n_host_wanted": n_want, "slots": slots, "lanes": lanes,
+                    f"{slots} chunk buffers",
+        "n_persist": n_persist, "n_host": n_host, "n_host_wanted": n_want, "slots": slots,
         "link_bytes_per_direction": link_bytes, "steps": K, "warmup": warmup,
         "link_GBps_per_direction": round(per_dir, 2), "ms_per_step": round(1e3 * t_step, 2),
         "bare_link_GBps": bare,
@@ -675,6 +675,25 @@ def brief(d):
     return out
 
 
+OTHER_CONFIGS = ("gpt2_block_768", "gpt2_xl_outliers", "llama_7b_fp16_loss_scaling", "llama_13b_half_in_pinned_host_memory")
+
+
+def run_other_config(name, with_cpu):
+    """One of the benchmark's other configurations, in this (fresh) process; returns its figures."""
+    if name == "gpt2_block_768":
+        d = brief(run_resident("gpt2_block_768", 300, 30, graph=True, calib=False))
+        d["note"] = ("0.13 GB of state: lives in the 256 MB Infinity Cache and is launch-bound; effective GB/s, "
+                     "not an HBM figure")
+        return d
+    if name == "gpt2_xl_outliers":
+        return brief(run_resident("gpt2_xl", 20, 5, calib=True, cpu_one_thread_chunks=3 if with_cpu else 0))
+    if name == "llama_7b_fp16_loss_scaling":
+        return brief(run_resident("llama_7b", 10, 3, fp16=True, calib=True))
+    if name == "llama_13b_half_in_pinned_host_memory":
+        return run_split(2, 1, slots=3, host_update=True)
+    raise ValueError(name)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -703,12 +722,12 @@ def main() -> int:
                          "pinned host memory through pt_chunk_stream_step")
     ap.add_argument("--host-chunks", type=int, default=0, help="--stream: host-resident chunks (default: all of the second half)")
     ap.add_argument("--slots", type=int, default=3, help="--stream: device chunk buffers")
-    ap.add_argument("--lanes", type=int, default=1, help="--stream: copy streams per direction (1 or 2)")
     ap.add_argument("--host-update", action="store_true",
                     help="--stream: also time the paper's placement, host chunks updated by host threads")
     ap.add_argument("--model", action="store_true",
                     help="--stream: fit the OPTIM-phase cost model on this box and validate it on held-out splits")
     ap.add_argument("--host-threads", type=int, default=0, help="--host-update: threads (default: all cores)")
+    ap.add_argument("--one-config", default="", choices=[""] + list(OTHER_CONFIGS), help=argparse.SUPPRESS)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -722,8 +741,12 @@ def main() -> int:
     torch.cuda.set_device(0)
     B.lib()
 
+    if args.one_config:
+        print(json.dumps(run_other_config(args.one_config, not args.no_cpu_baseline)), flush=True)
+        return 0
+
     if args.stream:
-        d = run_split(args.steps if args.steps != 20 else 3, min(args.warmup, 1), slots=args.slots, lanes=args.lanes,
+        d = run_split(args.steps if args.steps != 20 else 3, min(args.warmup, 1), slots=args.slots,
                       host_chunks=args.host_chunks, host_update=args.host_update, host_threads=args.host_threads, model=args.model)
         out = {"metric": "streamed chunked AdamW step: host-link GB/s per direction (both directions busy) + ms/step",
                "value": d["link_GBps_per_direction"], "unit": "GB/s per direction", "n_gpus": 1, "steps": d["steps"],
@@ -752,16 +775,24 @@ def main() -> int:
             out[k] = d[k]
 
     if headline and not args.headline_only:
-        # the other benchmark configurations, each bounded to a few seconds of timed work
+        # The other benchmark configurations, each bounded to a few seconds of timed work and each in a fresh
+        # process of its own, one after the other: what a configuration measures must not depend on what ran
+        # before it in this process (the physical placement of its arenas, and which hardware queues its side
+        # streams get - the streamed step moved 28 instead of 48 GB/s per direction when it ran fourth in one
+        # process).  This process has released its device memory and only waits meanwhile.
+        release()
         others = {}
         t_o = time.time()
-        others["gpt2_block_768"] = brief(run_resident("gpt2_block_768", 200, 20, graph=True, calib=False))
-        others["gpt2_block_768"]["note"] = ("0.13 GB of state: lives in the 256 MB Infinity Cache and is launch-bound; "
-                                            "effective GB/s, not an HBM figure")
-        others["gpt2_xl_outliers"] = brief(run_resident("gpt2_xl", 20, 5, calib=True, cpu_one_thread_chunks=0 if args.no_cpu_baseline else 3))
-        others["llama_7b_fp16_loss_scaling"] = brief(run_resident("llama_7b", 10, 3, fp16=True, calib=True))
-        split = run_split(2, 1, slots=3, lanes=args.lanes, host_update=True)
-        others["llama_13b_half_in_pinned_host_memory"] = split
+        for name in OTHER_CONFIGS:
+            extra = ["--no-cpu-baseline"] if args.no_cpu_baseline else []
+            res = subprocess.run([sys.executable, os.path.abspath(__file__), "--one-config", name] + extra,
+                                 stdout=subprocess.PIPE, text=True)
+            lines = [l for l in res.stdout.splitlines() if l.startswith("{")]
+            if res.returncode != 0 or not lines:
+                others[name] = {"error": f"child process exited with code {res.returncode}"}
+                log(f"[bench] configuration {name} failed (exit code {res.returncode})")
+                continue
+            others[name] = json.loads(lines[-1])
         out["other_configs"] = others
         log(f"[bench] other configurations measured in {time.time() - t_o:.1f} s")
     print(json.dumps(out), flush=True)

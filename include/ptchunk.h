@@ -135,12 +135,10 @@ int pt_ctx_set_no_decay(pt_ctx* ctx, const pt_segment* segs, uint32_t n_segs);
 /* Options (host state only, take effect at the next call).  Launch shape - none of these
  * changes a result bit:
  *   "adamw_grid"    workgroups of the update kernel; 0 = the library's default
+ *   "adamw_threads" workgroup size of the update kernel: 256, 512, or 0 = the library chooses by launch size (default)
  *   "adamw_unroll"  4-element units a lane loads before it computes: 1, 2, 4 or 8
  *   "adamw_nt"      1 = non-temporal hints on the update's loads and stores (default), 0 = none
  *   "pack_tile_elems"  elements one workgroup of pack/unpack moves; read by pt_pack_plan_create
- *   "stream_lanes"  copy streams per direction of the streamed path: 1 (default), or 2 - gradient +
- *                   master on one upload stream and momentum + variance on another, likewise on the
- *                   way back.  Choose before pt_stream_reserve (PT_ERR_STATE afterwards).
  * Gradient storage (variants of the path; the paper's gradients are the 16-bit array):
  *   "grad_fp32"     1 = the gradient chunks of this context hold fp32 (micro-batches accumulated
  *                   by pt_chunk_accum_grads): every `grad` / `h_grad` argument of the norm, the
@@ -322,7 +320,10 @@ int pt_stream_reserve(pt_ctx* ctx, uint32_t n_slots);
  * as round-to-nearest-even(master), which is what it held if it was produced by
  * this library or initialised from the master weights.
  * h_*: host arrays of n_chunks PINNED pointers (entry i is chunk first_chunk+i).
- * Requires pt_stream_reserve and a finalized norm in this step. */
+ * Requires pt_stream_reserve and a finalized norm in this step.
+ * The upload and offload streams want hardware queues of their own: in a process that holds many other
+ * streams (HIP maps streams onto GPU_MAX_HW_QUEUES hardware queues, 4 by default) the two directions can
+ * end up behind each other, and the link then carries one direction at a time. */
 int pt_chunk_stream_step(pt_ctx* ctx, const pt_hparams* hp, uint32_t first_chunk, uint32_t n_chunks,
                          const void* const* h_grad, float* const* h_master, float* const* h_m,
                          float* const* h_v, void* const* h_param16, void* stream);

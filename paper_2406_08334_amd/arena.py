@@ -46,3 +46,4 @@ def spread_arenas(specs, device="cuda", gap_bytes: int | None = None, keep_free_
     del spacers
     torch.cuda.empty_cache()          # hands the spacers back to the driver; the arenas stay where they are
     return out
+

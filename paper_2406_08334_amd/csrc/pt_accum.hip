@@ -169,7 +169,8 @@ extern "C" int pt_chunk_accum_grads(pt_ctx* ctx, const pt_pack_plan* plan, float
                      ctx->d_state, plan->d_tile_sq, plan->d_tile_flag);
   PT_LAUNCH_CHECK(ctx, "k_accum");
   if (take_norm) {
-    rc = pt_launch_chunk_reduce(ctx, plan->d_tile_sq, plan->d_tile_flag, plan->d_chunk_tile_begin, 0, ctx->C, 0, st);
+    rc = pt_launch_chunk_reduce(ctx, plan->d_tile_sq, plan->d_tile_flag, plan->d_chunk_tile_begin, 0, ctx->C, 0, st, plan,
+                                plan->n_tiles, uint32_t(plan->touched.size()));
     if (rc != PT_OK) return rc;
     for (uint32_t c : plan->touched) ctx->chunk_fresh[c] = 1;
   }

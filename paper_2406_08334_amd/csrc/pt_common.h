@@ -55,7 +55,6 @@ enum PtRow : int {
 };
 
 constexpr uint32_t PT_MAX_SLOTS = 8;
-constexpr uint32_t PT_MAX_LANES = 2;           // copy streams per direction of the streamed path
 constexpr uint32_t PT_ADAMW_MIN_GRID = 16384;      // default grid of the update kernel: max(this, tiles / 3)
 constexpr uint32_t PT_ADAMW_DEFAULT_UNROLL = 4;
 constexpr uint32_t PT_NORM_BLOCK_ELEMS = 32768;  // elements one block of the norm kernel reduces
@@ -81,6 +80,17 @@ struct pt_pack_plan {
 
 namespace pt_host { class Pool; }
 
+// A per-chunk reduction of partial sums that has been put off (see pt_norm.hip).
+struct PtPendingReduce {
+  bool active = false;
+  const double* part = nullptr;
+  const uint32_t* flag = nullptr;
+  const uint32_t* tile_begin = nullptr;
+  uint32_t first = 0, n = 0, per_chunk = 0;
+  hipStream_t stream = nullptr;          // where it was asked for (used if the plan goes away first)
+  const pt_pack_plan* plan = nullptr;    // owner of part / flag / tile_begin
+};
+
 struct pt_ctx {
   int device = 0;
   int dtype = PT_BF16;
@@ -91,6 +101,7 @@ struct pt_ctx {
   // launch-shape options (pt_ctx_set_option)
   uint32_t opt_adamw_grid = 0;      // workgroups of the update kernel; 0 = max(PT_ADAMW_MIN_GRID, tiles / 3)
   uint32_t opt_adamw_unroll = PT_ADAMW_DEFAULT_UNROLL;  // 4-element units per lane per tile: 1, 2, 4 or 8
+  uint32_t opt_adamw_threads = 0;   // workgroup size of the update kernel: 256, 512, or 0 = by launch size (pt_adamw_threads)
   uint32_t opt_adamw_nt = 1;        // non-temporal hints on the update's loads and stores
   uint32_t opt_pack_tile_elems = PT_PACK_TILE_ELEMS;  // read when a pack plan is created
   bool scaler = false;
@@ -109,17 +120,16 @@ struct pt_ctx {
   std::vector<uint8_t> chunk_fresh;     // [C] 1 = the chunk's sum of squares was taken in this step (since pt_step_end)
   bool norm_finalized = false;
   bool prepared = false;
+  PtPendingReduce pend_reduce;          // scalar work put off to be fused into one launch (pt_norm.hip)
+  bool pend_finalize = false;
   pt_hparams prepared_hp{};
 
   // streamed path
   uint32_t n_slots = 0;
   void* slot_mem[PT_MAX_SLOTS] = {};
-  // A chunk's four arrays travel on `stream_lanes` upload streams and as many offload streams
-  // (lane 0: gradient + master up, master + param16 down; lane 1: momentum + variance both ways).
-  uint32_t stream_lanes = 1;            // option "stream_lanes": 1 or 2, chosen before pt_stream_reserve
-  hipStream_t s_up[PT_MAX_LANES] = {}, s_comp = nullptr, s_down[PT_MAX_LANES] = {};
+  hipStream_t s_up = nullptr, s_comp = nullptr, s_down = nullptr;
   hipEvent_t ev_fork = nullptr;
-  hipEvent_t ev_up[PT_MAX_LANES][PT_MAX_SLOTS] = {}, ev_k[PT_MAX_SLOTS] = {}, ev_down[PT_MAX_LANES][PT_MAX_SLOTS] = {};
+  hipEvent_t ev_up[PT_MAX_SLOTS] = {}, ev_k[PT_MAX_SLOTS] = {}, ev_down[PT_MAX_SLOTS] = {};
   bool slot_used[PT_MAX_SLOTS] = {};
   bool stream_pending = false;
   uint32_t last_slot = 0;
@@ -210,13 +220,16 @@ inline const uint64_t* pt_row(const pt_ctx* ctx, int row) {
 }
 
 // ---- implemented in pt_adamw.hip ------------------------------------------------------
-// Runs the scalar "prepare" kernel if this step's constants are not yet derived
-// from `hp`, then launches the update kernel over table columns
-// [first_col, first_col + n_cols).
-int pt_prepare_consts(pt_ctx* ctx, const pt_hparams* hp, hipStream_t stream);
 // recast_on_skip: on a skipped step rewrite param16 = RNE(master) instead of doing nothing.
 // mask_chunk0: chunk index (for the no-decay ranges) of table column first_col.
 // zero_grads: overwrite the gradient chunks with zeros once read (resident chunks only).
+// Workgroup size for an update launch over n_cols chunks: the option if set, else 512 for launches of 2^28
+// elements or more (measured equal or up to 1 % faster there) and 256 for small ones (launch-bound: more, smaller
+// workgroups start sooner).
+inline uint32_t pt_adamw_threads(const pt_ctx* ctx, uint32_t n_cols) {
+  if (ctx->opt_adamw_threads) return ctx->opt_adamw_threads;
+  return ctx->S * uint64_t(n_cols) >= (uint64_t(1) << 28) ? 512u : 256u;
+}
 int pt_launch_adamw(pt_ctx* ctx, uint32_t first_col, uint32_t n_cols, hipStream_t stream, bool recast_on_skip,
                     uint32_t mask_chunk0, bool zero_grads);
 
@@ -234,7 +247,16 @@ void pt_host_pool_destroy(pt_ctx* ctx);
 // with a context never pays the lookup inside a hot call.
 int pt_static_scratch_setup(void** out);
 // Sums per-block partials into per-chunk values.  uniform mode (tile_begin == NULL):
-// chunk first+i owns partials [i*per_chunk, (i+1)*per_chunk).
+// chunk first+i owns partials [i*per_chunk, (i+1)*per_chunk).  With a plan whose n_touched chunks and
+// n_partials partial sums are few, the reduction is put off and runs inside the launch that finalizes
+// the norm (plan == NULL: always at once).
 int pt_launch_chunk_reduce(pt_ctx* ctx, const double* part, const uint32_t* flag,
                            const uint32_t* tile_begin, uint32_t first, uint32_t n,
-                           uint32_t per_chunk, hipStream_t stream);
+                           uint32_t per_chunk, hipStream_t stream, const pt_pack_plan* plan, uint32_t n_partials,
+                           uint32_t n_touched);
+// Launches, on `stream`, whatever scalar work of the step has been put off (per-chunk reduction, finalize).
+// Every call that reads the step's scalars or replaces what is pending goes through this first.
+int pt_flush_pending(pt_ctx* ctx, hipStream_t stream);
+// Derives this step's update constants from `hp` if that has not happened yet - in one launch together
+// with any pending reduction and finalize.
+int pt_prepare_consts(pt_ctx* ctx, const pt_hparams* hp, hipStream_t stream);

@@ -188,6 +188,7 @@ extern "C" int pt_ctx_set_state(pt_ctx* ctx, int32_t step, double loss_scale, in
     return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_ctx_set_state: step, good_steps >= 0 and loss_scale >= 1 required");
   if (!ctx->scaler && loss_scale != 1.0)
     return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_ctx_set_state: context has no scaler, loss_scale must be 1");
+  if (int rc = pt_flush_pending(ctx, (hipStream_t)stream); rc != PT_OK) return rc;
   hipLaunchKernelGGL(k_set_state, dim3(1), dim3(1), 0, (hipStream_t)stream, ctx->d_state, step,
                      loss_scale, good_steps);
   PT_LAUNCH_CHECK(ctx, "k_set_state");
@@ -208,6 +209,11 @@ extern "C" int pt_ctx_set_option(pt_ctx* ctx, const char* name, int64_t value) {
     ctx->opt_adamw_unroll = uint32_t(value);
     return PT_OK;
   }
+  if (std::strcmp(name, "adamw_threads") == 0) {
+    if (value != 0 && value != 256 && value != 512) return pt_fail(ctx, PT_ERR_INVALID_ARG, "adamw_threads must be 0, 256 or 512");
+    ctx->opt_adamw_threads = uint32_t(value);
+    return PT_OK;
+  }
   if (std::strcmp(name, "pack_tile_elems") == 0) {
     if (value < 1024 || value > (1 << 26)) return pt_fail(ctx, PT_ERR_INVALID_ARG, "pack_tile_elems must be in [1024, 2^26]");
     ctx->opt_pack_tile_elems = uint32_t(value);
@@ -215,13 +221,6 @@ extern "C" int pt_ctx_set_option(pt_ctx* ctx, const char* name, int64_t value) {
   }
   if (std::strcmp(name, "adamw_nt") == 0) {
     ctx->opt_adamw_nt = value != 0;
-    return PT_OK;
-  }
-  if (std::strcmp(name, "stream_lanes") == 0) {
-    if (value < 1 || value > int64_t(PT_MAX_LANES)) return pt_fail(ctx, PT_ERR_INVALID_ARG, "stream_lanes must be 1 or 2");
-    if (ctx->n_slots && uint32_t(value) != ctx->stream_lanes)
-      return pt_fail(ctx, PT_ERR_STATE, "stream_lanes must be chosen before pt_stream_reserve (it creates the copy streams)");
-    ctx->stream_lanes = uint32_t(value);
     return PT_OK;
   }
   if (std::strcmp(name, "adamw_zero_grads") == 0) {
@@ -292,6 +291,7 @@ extern "C" int pt_step_override(pt_ctx* ctx, float grad_mult, int32_t found_inf,
   if (ctx->stream_pending)
     return pt_fail(ctx, PT_ERR_STATE, "pt_step_override: a streamed update is still open (its kernels read the step's "
                    "scalars); close the step with pt_step_end first");
+  if (int rc = pt_flush_pending(ctx, (hipStream_t)stream); rc != PT_OK) return rc;   // a computed norm, if any, comes first
   hipLaunchKernelGGL(k_override, dim3(1), dim3(1), 0, (hipStream_t)stream, ctx->d_state, grad_mult,
                      found_inf ? 1 : 0);
   PT_LAUNCH_CHECK(ctx, "k_override");
@@ -304,11 +304,11 @@ extern "C" int pt_step_end(pt_ctx* ctx, void* stream) {
   if (!ctx) return PT_ERR_INVALID_ARG;
   hipStream_t st = (hipStream_t)stream;
   if (ctx->stream_pending) {
-    // offloads complete in order on each offload stream: the last event recorded on it covers them all
-    for (uint32_t l = 0; l < ctx->stream_lanes; ++l)
-      PT_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_down[l][ctx->last_slot], 0));
+    // offloads complete in order on one stream: the last one recorded covers them all
+    PT_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_down[ctx->last_slot], 0));
     ctx->stream_pending = false;
   }
+  if (int rc = pt_flush_pending(ctx, st); rc != PT_OK) return rc;     // a step without an update still needs its found_inf
   hipLaunchKernelGGL(k_step_end, dim3(1), dim3(1), 0, st, ctx->d_state);
   PT_LAUNCH_CHECK(ctx, "k_step_end");
   ctx->norm_finalized = false;
@@ -319,6 +319,7 @@ extern "C" int pt_step_end(pt_ctx* ctx, void* stream) {
 
 extern "C" int pt_step_report_read(pt_ctx* ctx, pt_step_report* out, void* stream) {
   if (!ctx || !out) return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_step_report_read: NULL argument");
+  if (int rc = pt_flush_pending(ctx, (hipStream_t)stream); rc != PT_OK) return rc;
   PtDevState h;
   PT_HIP(ctx, hipMemcpyAsync(&h, ctx->d_state, sizeof h, hipMemcpyDeviceToHost, (hipStream_t)stream));
   PT_HIP(ctx, hipStreamSynchronize((hipStream_t)stream));
@@ -330,6 +331,7 @@ extern "C" int pt_step_report_read(pt_ctx* ctx, pt_step_report* out, void* strea
 
 extern "C" int pt_update_consts_read(pt_ctx* ctx, pt_update_consts* out, void* stream) {
   if (!ctx || !out) return pt_fail(ctx, PT_ERR_INVALID_ARG, "pt_update_consts_read: NULL argument");
+  if (int rc = pt_flush_pending(ctx, (hipStream_t)stream); rc != PT_OK) return rc;
   PtDevState h;
   PT_HIP(ctx, hipMemcpyAsync(&h, ctx->d_state, sizeof h, hipMemcpyDeviceToHost, (hipStream_t)stream));
   PT_HIP(ctx, hipStreamSynchronize((hipStream_t)stream));

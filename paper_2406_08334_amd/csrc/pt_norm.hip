@@ -174,9 +174,7 @@ k_chunk_reduce(const double* __restrict__ part, const uint32_t* __restrict__ fla
 
 // Sums the per-chunk values of all chunks in chunk order (single thread: C is a
 // few hundred at most) and publishes the step's scalars.
-__global__ void k_finalize(const double* __restrict__ chunk_sq, const uint32_t* __restrict__ chunk_flag,
-                           uint32_t C, PtDevState* st) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+__device__ __forceinline__ void finalize_body(const double* chunk_sq, const uint32_t* chunk_flag, uint32_t C, PtDevState* st) {
   double t = 0.0;
   uint32_t f = 0;
   for (uint32_t c = 0; c < C; ++c) { t += chunk_sq[c]; f |= chunk_flag[c]; }
@@ -186,15 +184,149 @@ __global__ void k_finalize(const double* __restrict__ chunk_sq, const uint32_t* 
   st->override_active = 0;
 }
 
+__global__ void k_finalize(const double* chunk_sq, const uint32_t* chunk_flag, uint32_t C, PtDevState* st) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  finalize_body(chunk_sq, chunk_flag, C, st);
+}
+
+// Derives the nine fp32 constants of this update from the fp64 hyper-parameters
+// and the step's device scalars (Adam bias correction with t = applied updates
+// + 1; clip coefficient min(1, c/(norm+1e-6)); unscale by the loss scale).
+__device__ __forceinline__ void prepare_body(PtDevState* st, const pt_hparams& hp) {
+  const double t = double(st->step + 1);
+  double clip = 1.0;
+  float gm;
+  if (st->override_active) {
+    gm = st->override_grad_mult;
+  } else {
+    if (hp.max_norm > 0.0) {
+      double c = hp.max_norm / (st->norm + 1e-6);
+      clip = c < 1.0 ? c : 1.0;
+    }
+    gm = float(clip / st->loss_scale);
+  }
+  st->clip_coef = clip;
+  st->c[0] = float(hp.beta1);
+  st->c[1] = float(hp.beta2);
+  st->c[2] = float(1.0 - hp.beta1);
+  st->c[3] = float(1.0 - hp.beta2);
+  st->c[4] = float(1.0 - hp.lr * hp.weight_decay);
+  st->c[5] = float(hp.lr / (1.0 - pow(hp.beta1, t)));
+  st->c[6] = float(1.0 / sqrt(1.0 - pow(hp.beta2, t)));
+  st->c[7] = float(hp.eps);
+  st->c[8] = gm;
+  st->skip = st->found_inf ? 1 : 0;
+}
+
+__global__ void k_prepare(PtDevState* st, pt_hparams hp) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  prepare_body(st, hp);
+}
+
+// The scalar work of a step in ONE launch, for small states where launches are what a step costs:
+// one block walks the chunks one after the other - each chunk's partial sums reduced exactly as
+// k_chunk_reduce does it - then its thread 0 sums the chunks (k_finalize) and derives the update's
+// constants (k_prepare).  Same operations in the same order as the three separate kernels.
+//   n_reduce == 0: no per-chunk reduction (already done);  do_finalize == 0: the norm is already final.
+__global__ void __launch_bounds__(NB_THREADS)
+k_reduce_finalize_prepare(const double* __restrict__ part, const uint32_t* __restrict__ flag,
+                          const uint32_t* __restrict__ tile_begin, uint32_t first, uint32_t n_reduce, uint32_t per_chunk,
+                          double* chunk_sq, uint32_t* chunk_flag, uint32_t C, PtDevState* st, pt_hparams hp,
+                          int do_finalize, int do_prepare) {
+  for (uint32_t i = 0; i < n_reduce; ++i) {
+    const uint32_t c = first + i;
+    uint32_t lo, hi;
+    if (tile_begin) { lo = tile_begin[c]; hi = tile_begin[c + 1]; if (lo == hi) continue; }
+    else { lo = i * per_chunk; hi = lo + per_chunk; }
+    double acc = 0.0;
+    uint32_t f = 0;
+    for (uint32_t k = lo + threadIdx.x; k < hi; k += NB_THREADS) { acc += part[k]; f |= flag[k]; }
+    pt_block_sum(acc, f);
+    if (threadIdx.x == 0) { chunk_sq[c] = acc; chunk_flag[c] = f; }
+    __syncthreads();                 // the reduction's LDS slots are reused by the next chunk
+  }
+  if (threadIdx.x != 0) return;
+  // thread 0 wrote every per-chunk value of this launch itself; the others come from earlier kernels
+  if (do_finalize) finalize_body(chunk_sq, chunk_flag, C, st);
+  if (do_prepare) prepare_body(st, hp);
+}
+
 }  // namespace
+
+// ---- scalar work of a step: launched at once, or deferred and fused -------------------------
+//
+// A step's scalar kernels (per-chunk reduction of the partial sums, finalize, prepare) are tiny;
+// for a small state their launches are most of the step.  So the finalize is always deferred to
+// the first call that needs its result - normally the update, which then derives its constants in
+// the same launch - and the per-chunk reduction of a pack / accumulate plan is deferred with it
+// when the plan is small enough for one block to walk (PT_FUSE_MAX_CHUNKS chunks,
+// PT_FUSE_MAX_PARTIALS partial sums).  Every call that reads or replaces what is pending flushes it
+// first (pt_flush_pending): results and their order are those of the separate kernels.
+
+constexpr uint32_t PT_FUSE_MAX_CHUNKS = 8;
+constexpr uint32_t PT_FUSE_MAX_PARTIALS = 16384;
+
+static int launch_reduce_now(pt_ctx* ctx, const PtPendingReduce& r, hipStream_t stream) {
+  if (r.n == 0) return PT_OK;
+  hipLaunchKernelGGL(k_chunk_reduce, dim3(r.n), dim3(NB_THREADS), 0, stream, r.part, r.flag, r.tile_begin,
+                     r.first, r.per_chunk, ctx->d_chunk_sq, ctx->d_chunk_flag);
+  PT_LAUNCH_CHECK(ctx, "k_chunk_reduce");
+  return PT_OK;
+}
+
+int pt_flush_pending(pt_ctx* ctx, hipStream_t stream) {
+  if (ctx->pend_reduce.active) {
+    ctx->pend_reduce.active = false;
+    int rc = launch_reduce_now(ctx, ctx->pend_reduce, stream);
+    if (rc != PT_OK) return rc;
+  }
+  if (ctx->pend_finalize) {
+    ctx->pend_finalize = false;
+    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(64), 0, stream, ctx->d_chunk_sq, ctx->d_chunk_flag, ctx->C, ctx->d_state);
+    PT_LAUNCH_CHECK(ctx, "k_finalize");
+  }
+  return PT_OK;
+}
 
 int pt_launch_chunk_reduce(pt_ctx* ctx, const double* part, const uint32_t* flag,
                            const uint32_t* tile_begin, uint32_t first, uint32_t n,
-                           uint32_t per_chunk, hipStream_t stream) {
+                           uint32_t per_chunk, hipStream_t stream, const pt_pack_plan* plan, uint32_t n_partials,
+                           uint32_t n_touched) {
   if (n == 0) return PT_OK;
-  hipLaunchKernelGGL(k_chunk_reduce, dim3(n), dim3(NB_THREADS), 0, stream, part, flag, tile_begin,
-                     first, per_chunk, ctx->d_chunk_sq, ctx->d_chunk_flag);
-  PT_LAUNCH_CHECK(ctx, "k_chunk_reduce");
+  // whatever is pending comes first: a later reduction of the same chunk replaces an earlier one
+  int rc = pt_flush_pending(ctx, stream);
+  if (rc != PT_OK) return rc;
+  PtPendingReduce r{true, part, flag, tile_begin, first, n, per_chunk, stream, plan};
+  if (plan && n_touched <= PT_FUSE_MAX_CHUNKS && n <= 64 && n_partials <= PT_FUSE_MAX_PARTIALS) {
+    ctx->pend_reduce = r;            // runs inside the launch that finalizes the norm
+    return PT_OK;
+  }
+  return launch_reduce_now(ctx, r, stream);
+}
+
+int pt_prepare_consts(pt_ctx* ctx, const pt_hparams* hp, hipStream_t stream) {
+  if (ctx->prepared) {
+    if (std::memcmp(&ctx->prepared_hp, hp, sizeof *hp) == 0) return PT_OK;
+    if (ctx->stream_pending)
+      return pt_fail(ctx, PT_ERR_STATE, "hyper-parameters changed while a streamed update of this step is in flight");
+  }
+  if (ctx->pend_reduce.active || ctx->pend_finalize) {
+    const PtPendingReduce r = ctx->pend_reduce;
+    const bool red = r.active;
+    hipLaunchKernelGGL(k_reduce_finalize_prepare, dim3(1), dim3(NB_THREADS), 0, stream, red ? r.part : nullptr,
+                       red ? r.flag : nullptr, red ? r.tile_begin : nullptr, red ? r.first : 0u, red ? r.n : 0u,
+                       red ? r.per_chunk : 0u, ctx->d_chunk_sq, ctx->d_chunk_flag, ctx->C, ctx->d_state, *hp,
+                       ctx->pend_finalize ? 1 : 0, 1);
+    PT_LAUNCH_CHECK(ctx, "k_reduce_finalize_prepare");
+    ctx->pend_reduce.active = false;
+    ctx->pend_finalize = false;
+  } else {
+    hipLaunchKernelGGL(k_prepare, dim3(1), dim3(1), 0, stream, ctx->d_state, *hp);
+    PT_LAUNCH_CHECK(ctx, "k_prepare");
+  }
+  PT_HIP(ctx, hipEventRecord(ctx->ev_scalar, stream));   // lets the host-side update read the scalars early
+  ctx->prepared = true;
+  ctx->prepared_hp = *hp;
   return PT_OK;
 }
 
@@ -222,7 +354,7 @@ extern "C" int pt_chunk_grad_sqnorm(pt_ctx* ctx, const void* const* grad_chunks,
                          ctx->S, ctx->d_state, ctx->d_norm_part, ctx->d_norm_flag);
     PT_LAUNCH_CHECK(ctx, "k_sqnorm");
     int rc2 = pt_launch_chunk_reduce(ctx, ctx->d_norm_part, ctx->d_norm_flag, nullptr, first_chunk, n_chunks,
-                                     ctx->norm_blocks, st);
+                                     ctx->norm_blocks, st, nullptr, 0, n_chunks);
     if (rc2 != PT_OK) return rc2;
     for (uint32_t c = first_chunk; c < first_chunk + n_chunks; ++c) ctx->chunk_fresh[c] = 1;
   }
@@ -237,9 +369,9 @@ extern "C" int pt_chunk_grad_sqnorm(pt_ctx* ctx, const void* const* grad_chunks,
                          "packed, accumulated or recomputed for it since the last pt_step_end); its old value would enter "
                          "the norm - finalize with PT_FINALIZE_CARRY if that is meant", c);
     }
-    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(64), 0, st, ctx->d_chunk_sq, ctx->d_chunk_flag, ctx->C,
-                       ctx->d_state);
-    PT_LAUNCH_CHECK(ctx, "k_finalize");
+    // The sum over the chunks runs with the first call that needs it: the update (in the launch that
+    // derives its constants), a read-back, or pt_step_end.
+    ctx->pend_finalize = true;
     ctx->norm_finalized = true;
     ctx->prepared = false;
   }

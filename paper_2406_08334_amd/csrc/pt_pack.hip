@@ -242,6 +242,9 @@ static int plan_create(pt_ctx* ctx, const pt_segment* segs, uint32_t n_segs, pt_
 
 extern "C" int pt_pack_plan_destroy(pt_pack_plan* plan) {
   if (!plan) return PT_OK;
+  // a reduction of this plan's partial sums that was put off runs now, before they are freed
+  if (plan->ctx && plan->ctx->pend_reduce.active && plan->ctx->pend_reduce.plan == plan)
+    (void)pt_flush_pending(plan->ctx, plan->ctx->pend_reduce.stream);
   (void)hipDeviceSynchronize();
   plan_free(plan);
   delete plan;
@@ -275,7 +278,8 @@ static int run_pack(pt_ctx* ctx, const pt_pack_plan* plan, const void* const* ch
                        ctx->d_state, plan->d_tile_sq, plan->d_tile_flag);
   PT_LAUNCH_CHECK(ctx, who);
   if (DIR == 0) {
-    rc = pt_launch_chunk_reduce(ctx, plan->d_tile_sq, plan->d_tile_flag, plan->d_chunk_tile_begin, 0, ctx->C, 0, st);
+    rc = pt_launch_chunk_reduce(ctx, plan->d_tile_sq, plan->d_tile_flag, plan->d_chunk_tile_begin, 0, ctx->C, 0, st, plan,
+                                plan->n_tiles, uint32_t(plan->touched.size()));
     if (rc != PT_OK) return rc;
     for (uint32_t c : plan->touched) ctx->chunk_fresh[c] = 1;
   }

@@ -21,18 +21,14 @@ static int reserve_slots(pt_ctx* ctx, uint32_t n_slots);
 
 // Gives back whatever a reservation (failed or complete) has created, so that the call can be repeated.
 void pt_stream_release(pt_ctx* ctx) {
-  for (uint32_t l = 0; l < PT_MAX_LANES; ++l) {
-    if (ctx->s_up[l]) { (void)hipStreamDestroy(ctx->s_up[l]); ctx->s_up[l] = nullptr; }
-    if (ctx->s_down[l]) { (void)hipStreamDestroy(ctx->s_down[l]); ctx->s_down[l] = nullptr; }
-    for (uint32_t s = 0; s < PT_MAX_SLOTS; ++s) {
-      if (ctx->ev_up[l][s]) { (void)hipEventDestroy(ctx->ev_up[l][s]); ctx->ev_up[l][s] = nullptr; }
-      if (ctx->ev_down[l][s]) { (void)hipEventDestroy(ctx->ev_down[l][s]); ctx->ev_down[l][s] = nullptr; }
-    }
-  }
+  if (ctx->s_up) { (void)hipStreamDestroy(ctx->s_up); ctx->s_up = nullptr; }
   if (ctx->s_comp) { (void)hipStreamDestroy(ctx->s_comp); ctx->s_comp = nullptr; }
+  if (ctx->s_down) { (void)hipStreamDestroy(ctx->s_down); ctx->s_down = nullptr; }
   if (ctx->ev_fork) { (void)hipEventDestroy(ctx->ev_fork); ctx->ev_fork = nullptr; }
   for (uint32_t s = 0; s < PT_MAX_SLOTS; ++s) {
+    if (ctx->ev_up[s]) { (void)hipEventDestroy(ctx->ev_up[s]); ctx->ev_up[s] = nullptr; }
     if (ctx->ev_k[s]) { (void)hipEventDestroy(ctx->ev_k[s]); ctx->ev_k[s] = nullptr; }
+    if (ctx->ev_down[s]) { (void)hipEventDestroy(ctx->ev_down[s]); ctx->ev_down[s] = nullptr; }
     if (ctx->slot_mem[s]) { (void)hipFree(ctx->slot_mem[s]); ctx->slot_mem[s] = nullptr; }
   }
 }
@@ -48,18 +44,16 @@ extern "C" int pt_stream_reserve(pt_ctx* ctx, uint32_t n_slots) {
 }
 
 static int reserve_slots(pt_ctx* ctx, uint32_t n_slots) {
-  for (uint32_t l = 0; l < ctx->stream_lanes; ++l) {
-    PT_HIP(ctx, hipStreamCreateWithFlags(&ctx->s_up[l], hipStreamNonBlocking));
-    PT_HIP(ctx, hipStreamCreateWithFlags(&ctx->s_down[l], hipStreamNonBlocking));
-  }
+  // upload, compute, offload: three streams created one after the other, each wants a hardware queue of
+  // its own (copies in the two directions overlap only then)
+  PT_HIP(ctx, hipStreamCreateWithFlags(&ctx->s_up, hipStreamNonBlocking));
   PT_HIP(ctx, hipStreamCreateWithFlags(&ctx->s_comp, hipStreamNonBlocking));
+  PT_HIP(ctx, hipStreamCreateWithFlags(&ctx->s_down, hipStreamNonBlocking));
   PT_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming));
   for (uint32_t s = 0; s < n_slots; ++s) {
-    for (uint32_t l = 0; l < ctx->stream_lanes; ++l) {
-      PT_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_up[l][s], hipEventDisableTiming));
-      PT_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_down[l][s], hipEventDisableTiming));
-    }
+    PT_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_up[s], hipEventDisableTiming));
     PT_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_k[s], hipEventDisableTiming));
+    PT_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_down[s], hipEventDisableTiming));
     hipError_t e = hipMalloc(&ctx->slot_mem[s], slot_bytes(ctx));
     if (e != hipSuccess)
       return pt_fail(ctx, e == hipErrorOutOfMemory ? PT_ERR_NOMEM : PT_ERR_HIP,
@@ -106,35 +100,31 @@ extern "C" int pt_chunk_stream_step(pt_ctx* ctx, const pt_hparams* hp, uint32_t 
   int rc = pt_prepare_consts(ctx, hp, st);
   if (rc != PT_OK) return rc;
   // side streams start after everything already enqueued on the caller's stream
-  const uint32_t L = ctx->stream_lanes;
   PT_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
-  for (uint32_t l = 0; l < L; ++l) PT_HIP(ctx, hipStreamWaitEvent(ctx->s_up[l], ctx->ev_fork, 0));
+  PT_HIP(ctx, hipStreamWaitEvent(ctx->s_up, ctx->ev_fork, 0));
   PT_HIP(ctx, hipStreamWaitEvent(ctx->s_comp, ctx->ev_fork, 0));
 
   const size_t S = ctx->S;
-  const uint32_t hi = L - 1;                 // the lane that carries momentum and variance
   for (uint32_t i = 0; i < n_chunks; ++i) {
     const uint32_t s = i % ctx->n_slots;
-    // upload: the slot must have been offloaded by its previous tenant (on every offload stream)
-    if (ctx->slot_used[s])
-      for (uint32_t lu = 0; lu < L; ++lu)
-        for (uint32_t ld = 0; ld < L; ++ld) PT_HIP(ctx, hipStreamWaitEvent(ctx->s_up[lu], ctx->ev_down[ld][s], 0));
-    PT_HIP(ctx, hipMemcpyAsync(slot_grad(ctx, s), h_grad[i], grad_bytes(ctx) * S, hipMemcpyHostToDevice, ctx->s_up[0]));
-    PT_HIP(ctx, hipMemcpyAsync(slot_master(ctx, s), h_master[i], 4 * S, hipMemcpyHostToDevice, ctx->s_up[0]));
-    PT_HIP(ctx, hipMemcpyAsync(slot_m(ctx, s), h_m[i], 4 * S, hipMemcpyHostToDevice, ctx->s_up[hi]));
-    PT_HIP(ctx, hipMemcpyAsync(slot_v(ctx, s), h_v[i], 4 * S, hipMemcpyHostToDevice, ctx->s_up[hi]));
-    for (uint32_t l = 0; l < L; ++l) PT_HIP(ctx, hipEventRecord(ctx->ev_up[l][s], ctx->s_up[l]));
+    // upload: the slot must have been offloaded by its previous tenant
+    if (ctx->slot_used[s]) PT_HIP(ctx, hipStreamWaitEvent(ctx->s_up, ctx->ev_down[s], 0));
+    PT_HIP(ctx, hipMemcpyAsync(slot_grad(ctx, s), h_grad[i], grad_bytes(ctx) * S, hipMemcpyHostToDevice, ctx->s_up));
+    PT_HIP(ctx, hipMemcpyAsync(slot_master(ctx, s), h_master[i], 4 * S, hipMemcpyHostToDevice, ctx->s_up));
+    PT_HIP(ctx, hipMemcpyAsync(slot_m(ctx, s), h_m[i], 4 * S, hipMemcpyHostToDevice, ctx->s_up));
+    PT_HIP(ctx, hipMemcpyAsync(slot_v(ctx, s), h_v[i], 4 * S, hipMemcpyHostToDevice, ctx->s_up));
+    PT_HIP(ctx, hipEventRecord(ctx->ev_up[s], ctx->s_up));
     // update on the slot
-    for (uint32_t l = 0; l < L; ++l) PT_HIP(ctx, hipStreamWaitEvent(ctx->s_comp, ctx->ev_up[l][s], 0));
+    PT_HIP(ctx, hipStreamWaitEvent(ctx->s_comp, ctx->ev_up[s], 0));
     if ((rc = pt_launch_adamw(ctx, ctx->C + s, 1, ctx->s_comp, true, first_chunk + i, false)) != PT_OK) return rc;
     PT_HIP(ctx, hipEventRecord(ctx->ev_k[s], ctx->s_comp));
     // offload
-    for (uint32_t l = 0; l < L; ++l) PT_HIP(ctx, hipStreamWaitEvent(ctx->s_down[l], ctx->ev_k[s], 0));
-    PT_HIP(ctx, hipMemcpyAsync(h_master[i], slot_master(ctx, s), 4 * S, hipMemcpyDeviceToHost, ctx->s_down[0]));
-    PT_HIP(ctx, hipMemcpyAsync(h_param16[i], slot_p16(ctx, s), 2 * S, hipMemcpyDeviceToHost, ctx->s_down[0]));
-    PT_HIP(ctx, hipMemcpyAsync(h_m[i], slot_m(ctx, s), 4 * S, hipMemcpyDeviceToHost, ctx->s_down[hi]));
-    PT_HIP(ctx, hipMemcpyAsync(h_v[i], slot_v(ctx, s), 4 * S, hipMemcpyDeviceToHost, ctx->s_down[hi]));
-    for (uint32_t l = 0; l < L; ++l) PT_HIP(ctx, hipEventRecord(ctx->ev_down[l][s], ctx->s_down[l]));
+    PT_HIP(ctx, hipStreamWaitEvent(ctx->s_down, ctx->ev_k[s], 0));
+    PT_HIP(ctx, hipMemcpyAsync(h_master[i], slot_master(ctx, s), 4 * S, hipMemcpyDeviceToHost, ctx->s_down));
+    PT_HIP(ctx, hipMemcpyAsync(h_m[i], slot_m(ctx, s), 4 * S, hipMemcpyDeviceToHost, ctx->s_down));
+    PT_HIP(ctx, hipMemcpyAsync(h_v[i], slot_v(ctx, s), 4 * S, hipMemcpyDeviceToHost, ctx->s_down));
+    PT_HIP(ctx, hipMemcpyAsync(h_param16[i], slot_p16(ctx, s), 2 * S, hipMemcpyDeviceToHost, ctx->s_down));
+    PT_HIP(ctx, hipEventRecord(ctx->ev_down[s], ctx->s_down));
     ctx->slot_used[s] = true;
     ctx->last_slot = s;
     ctx->stream_pending = true;

@@ -27,12 +27,13 @@ def awkward_runs(S):
 
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
-@pytest.mark.parametrize("unroll", [4, 1, 8])
-def test_masked_kernel_is_bit_exact_against_the_masked_f32_sequence(orc, dtype, unroll):
+@pytest.mark.parametrize("unroll,threads", [(4, 512), (1, 512), (8, 512), (4, 256), (8, 256)])
+def test_masked_kernel_is_bit_exact_against_the_masked_f32_sequence(orc, dtype, unroll, threads):
     S, C = TILE * 5 + 40, 4
     st = ChunkedState([S * C - 5], S, dtype=dtype)
     try:
         B.pt_ctx_set_option(st.ctx, "adamw_unroll", unroll)
+        B.pt_ctx_set_option(st.ctx, "adamw_threads", threads)
         hp_b, hp_o, _ = hp_pair()
         mask = st.set_no_decay(runs=awkward_runs(S))
         assert 0 < mask.sum() < mask.size

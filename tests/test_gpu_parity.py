@@ -157,10 +157,12 @@ def run_oracle_f32seq(orc, consts, st_host, dtype, no_decay=None):
 
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
-@pytest.mark.parametrize("S,C", [(4096 * 3 + 40, 3), (8, 2), (16384 * 8, 2), (4096, 1)])
-def test_adamw_kernel_isolated_is_bit_exact_against_f32_sequence(orc, dtype, S, C):
+@pytest.mark.parametrize("S,C,threads", [(4096 * 3 + 40, 3, 512), (8, 2, 512), (16384 * 8, 2, 512), (4096, 1, 512),
+                                         (4096 * 3 + 40, 3, 256), (16384 * 8 + 2048, 2, 256)])
+def test_adamw_kernel_isolated_is_bit_exact_against_f32_sequence(orc, dtype, S, C, threads):
     st = ChunkedState([S * C - 5], S, dtype=dtype)
     try:
+        B.pt_ctx_set_option(st.ctx, "adamw_threads", threads)
         hp_b, hp_o, hpd = hp_pair()
         host = st.host_state()
         h64 = {k: a.copy() for k, a in host.items()}
@@ -398,7 +400,7 @@ def test_loss_scale_growth_on_device(orc):
 # ------------------------------------------------------------------- streamed == resident
 
 def run_mixed(sizes, S, n_persist, n_slots, steps, dtype=torch.bfloat16, scaler=None, inf_step=None, host_update=False,
-              no_decay_runs=None, orc=None, lanes=1):
+              no_decay_runs=None, orc=None):
     """Chunks [0, n_persist) resident, the rest in pinned host memory: streamed through chunk buffers, or
     (host_update) updated by host threads.  With `orc` the oracle takes every step beside the device on
     the same seeded inputs (its own pack, norm, constants and fp32 sequence) and the final state of ALL
@@ -418,7 +420,6 @@ def run_mixed(sizes, S, n_persist, n_slots, steps, dtype=torch.bfloat16, scaler=
             ost = orc.new_state(sc_o)
         if n_persist < C:
             if not host_update:
-                B.pt_ctx_set_option(st.ctx, "stream_lanes", lanes)
                 B.pt_stream_reserve(st.ctx, n_slots)
             for name, arena in (("g16", st.g16), ("p16", st.p16), ("w", st.w), ("m", st.m), ("v", st.v)):
                 host[name] = [torch.empty(S, dtype=arena.dtype).pin_memory() for _ in range(n_persist, C)]
@@ -471,13 +472,12 @@ def run_mixed(sizes, S, n_persist, n_slots, steps, dtype=torch.bfloat16, scaler=
 def test_streamed_and_host_updated_chunks_equal_the_oracle_and_the_resident_bits(orc, dtype, scaler, inf_step):
     sizes, S = [6 * 40_000 - 24], 40_000                        # 6 chunks, last one padded
     ref = run_mixed(sizes, S, 6, 2, steps=3, dtype=dtype, scaler=scaler, inf_step=inf_step, orc=orc)
-    for n_persist, n_slots, lanes in ((3, 2, 1), (0, 2, 1), (0, 3, 1), (2, 3, 1), (5, 2, 1), (0, 2, 2), (2, 3, 2)):
-        got = run_mixed(sizes, S, n_persist, n_slots, steps=3, dtype=dtype, scaler=scaler, inf_step=inf_step, orc=orc,
-                        lanes=lanes)
+    for n_persist, n_slots in ((3, 2), (0, 2), (0, 3), (2, 3), (5, 2)):
+        got = run_mixed(sizes, S, n_persist, n_slots, steps=3, dtype=dtype, scaler=scaler, inf_step=inf_step, orc=orc)
         for name in ("p16", "w", "m", "v"):
             assert torch.equal(got[name].view(torch.int16 if got[name].element_size() == 2 else torch.int32),
                                ref[name].view(torch.int16 if ref[name].element_size() == 2 else torch.int32)), \
-                (name, n_persist, n_slots, lanes)
+                (name, n_persist, n_slots)
         assert got["report"].step == ref["report"].step and got["report"].loss_scale == ref["report"].loss_scale
     # the paper's placement: non-persistent chunks updated by host threads, same bits again
     for n_persist in (3, 0, 5):
