@@ -187,7 +187,7 @@ int main(int argc, char** argv) {
   // standalone norm over all chunks (reads 2 bytes per element)
   {
     CHECK_HIP(hipEventRecord(e[0], st));
-    CHECK_PT(ctx, pt_chunk_grad_sqnorm(ctx, g.data(), 0, C, 1, st));
+    CHECK_PT(ctx, pt_chunk_grad_sqnorm(ctx, g.data(), 0, C, n_host ? PT_FINALIZE_CARRY : PT_FINALIZE_STRICT, st));
     CHECK_HIP(hipEventRecord(e[1], st));
     CHECK_HIP(hipStreamSynchronize(st));
     float t;
