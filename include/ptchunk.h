@@ -37,7 +37,11 @@
  *    path.
  *  - Sizes and offsets are in ELEMENTS.  chunk_elems must be a multiple of 8.
  *    Every chunk base pointer must be 16-byte aligned.
- *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  The calls of one
+ *    step work on the context's shared scratch in call order: give them one stream, or make
+ *    each call's stream wait (event) for the previous call's.  The tiny scalar kernels of a call
+ *    (per-chunk sums, the final norm) may be enqueued later, by the next call of the step that
+ *    needs them and on THAT call's stream - which is behind the earlier call under this rule.
  *  - A context is not thread-safe; use one per optimizer instance.
  */
 #ifndef PTCHUNK_H

@@ -30,6 +30,24 @@ from tolerance import ScaleTracker, check_p16, far_cap
 pytestmark = pytest.mark.gpu
 
 
+def say(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(autouse=True)
+def progress_lines_bypass_capture(capsys):
+    """These tests run for minutes: their progress lines go to the real stdout even when pytest captures
+    output, so that whoever watches the run sees that it is alive."""
+    global say
+
+    def uncaptured(msg):
+        with capsys.disabled():
+            print(msg, flush=True)
+    say = uncaptured
+    yield
+    say = lambda msg: print(msg, flush=True)
+
+
 class FullState:
     def __init__(self, workload, dtype, scaler=None):
         table, S = shapes.workload(workload)
@@ -190,8 +208,8 @@ class SplitState(FullState):
             try:
                 got = [torch.zeros(S, dtype=dt, pin_memory=True) for _, dt in kinds]
             except RuntimeError as e:
-                print(f"[fullsize] pinning stopped after {i} host chunks ({16 * i * S / 1e9:.1f} GB pinned; host RAM "
-                      f"{host_memory_total_gb():.0f} GB): {str(e).splitlines()[0][:120]}", flush=True)
+                say(f"[fullsize] pinning stopped after {i} host chunks ({16 * i * S / 1e9:.1f} GB pinned; host RAM "
+                    f"{host_memory_total_gb():.0f} GB): {str(e).splitlines()[0][:120]}")
                 got = None
                 for name in self.host:
                     del self.host[name][max(0, i - 4):]
@@ -200,10 +218,12 @@ class SplitState(FullState):
                 break
             for (name, _), t in zip(kinds, got):
                 self.host[name].append(t)
+            if i % 16 == 15:
+                say(f"[fullsize] {i + 1} host chunks pinned")
         n_host = len(self.host["w"])
         assert n_host >= 8, "the box pins fewer than 8 host chunks"
-        print(f"[fullsize] {n_resident} resident chunks, {n_host} of {n_host_wanted} host chunks pinned "
-              f"({16 * n_host * S / 1e9:.1f} GB; host RAM {host_memory_total_gb():.0f} GB)", flush=True)
+        say(f"[fullsize] {n_resident} resident chunks, {n_host} of {n_host_wanted} host chunks pinned "
+            f"({16 * n_host * S / 1e9:.1f} GB; host RAM {host_memory_total_gb():.0f} GB)")
         C = self.C = n_resident + n_host
         assert C < c_all, "the cut must fall on a chunk boundary before the padded last chunk"
         self.n_resident, self.n_host = n_resident, n_host
@@ -294,7 +314,7 @@ def check_every_chunk_after_the_first_step(st, consts):
         for name, want in (("w", w), ("m", m), ("v", v), ("p16", p)):
             assert_same_bits(got[name], want, (name, "chunk", c, "first step, every element"))
         if c % 10 == 0 or c == st.C - 1:
-            print(f"[fullsize] first step, every element: chunk {c + 1}/{st.C} ok ({time.time() - t0:.0f} s)", flush=True)
+            say(f"[fullsize] first step, every element: chunk {c + 1}/{st.C} ok ({time.time() - t0:.0f} s)")
 
 
 def run_full(workload, dtype, steps, scaler_b=None, scaler_o=None, inf_step=None, outlier_every=0, sample=None,
@@ -315,7 +335,7 @@ def run_full(workload, dtype, steps, scaler_b=None, scaler_o=None, inf_step=None
                              trk=ScaleTracker(h["w"], h["m"], hpd))
         out = []
         for s in range(1, steps + 1):
-            print(f"[fullsize] {workload} {dtype} step {s}/{steps}", flush=True)
+            say(f"[fullsize] {workload} {dtype} step {s}/{steps}")
             sigma = ost.loss_scale
             synth.normal_16(synth.SEED_GRADS, s, 0, 0, N, 1e-3, dtype, "cuda", scale=sigma,
                             outlier_every=outlier_every, out=st.grad_src)
@@ -363,7 +383,7 @@ def run_full(workload, dtype, steps, scaler_b=None, scaler_o=None, inf_step=None
             assert consts[:8].tobytes() == dev_c[:8].tobytes()
             assert abs(int(consts[8:].view(np.int32)[0]) - int(dev_c[8:].view(np.int32)[0])) <= 1
             if consts[8] != dev_c[8]:
-                print(f"[fullsize] step {s}: grad_mult one ulp apart, taking the device's", flush=True)
+                say(f"[fullsize] step {s}: grad_mult one ulp apart, taking the device's")
                 consts[8] = dev_c[8]
             if s == 1 and every_chunk:
                 check_every_chunk_after_the_first_step(st, consts)
