@@ -141,7 +141,8 @@ int pt_ctx_set_no_decay(pt_ctx* ctx, const pt_segment* segs, uint32_t n_segs);
  *   "adamw_grid"    workgroups of the update kernel; 0 = the library's default
  *   "adamw_threads" workgroup size of the update kernel: 256, 512, or 0 = the library chooses by launch size (default)
  *   "adamw_unroll"  4-element units a lane loads before it computes: 1, 2, 4 or 8
- *   "adamw_nt"      1 = non-temporal hints on the update's loads and stores (default), 0 = none
+ *   "adamw_nt"      non-temporal hints on the update's loads and stores: 1 = always, 0 = never, 2 = the library
+ *                   chooses by launch size (default): none while the launch's state fits the 256 MB Infinity Cache
  *   "pack_tile_elems"  elements one workgroup of pack/unpack moves; read by pt_pack_plan_create
  * Gradient storage (variants of the path; the paper's gradients are the 16-bit array):
  *   "grad_fp32"     1 = the gradient chunks of this context hold fp32 (micro-batches accumulated

@@ -372,7 +372,7 @@ int pt_launch_adamw(pt_ctx* ctx, uint32_t first_col, uint32_t n_cols, hipStream_
   uint32_t want = ctx->opt_adamw_grid > 0 ? ctx->opt_adamw_grid : (total + 2) / 3;
   if (ctx->opt_adamw_grid == 0 && want < PT_ADAMW_MIN_GRID) want = PT_ADAMW_MIN_GRID;
   dim3 grid(want < total ? want : total);
-  const bool nt = ctx->opt_adamw_nt != 0, masked = ctx->d_nd_begin != nullptr;
+  const bool nt = pt_adamw_nt(ctx, n_cols), masked = ctx->d_nd_begin != nullptr;
   adamw_kernel_t kern = ctx->dtype == PT_BF16 ? pick_kernel<PT_BF16>(threads, unroll, nt, masked, ctx->grad_f32)
                                               : pick_kernel<PT_FP16>(threads, unroll, nt, masked, ctx->grad_f32);
   hipLaunchKernelGGL(kern, grid, dim3(threads), 0, stream, ctx->d_table, ctx->table_cols, first_col, n_cols,
@@ -429,7 +429,7 @@ extern "C" int pt_calib_adamw_pattern(pt_ctx* ctx, uint32_t first_chunk, uint32_
   uint32_t want = ctx->opt_adamw_grid > 0 ? ctx->opt_adamw_grid : (total + 2) / 3;      // as pt_launch_adamw
   if (ctx->opt_adamw_grid == 0 && want < PT_ADAMW_MIN_GRID) want = PT_ADAMW_MIN_GRID;
   dim3 grid(want < total ? want : total);
-  const bool nt = ctx->opt_adamw_nt != 0;
+  const bool nt = pt_adamw_nt(ctx, n_chunks);
   pattern_kernel_t kern = ctx->dtype == PT_BF16 ? pick_pattern<PT_BF16>(threads, unroll, nt)
                                                 : pick_pattern<PT_FP16>(threads, unroll, nt);
   hipLaunchKernelGGL(kern, grid, dim3(threads), 0, (hipStream_t)stream, ctx->d_table, ctx->table_cols, first_chunk,

@@ -220,7 +220,8 @@ extern "C" int pt_ctx_set_option(pt_ctx* ctx, const char* name, int64_t value) {
     return PT_OK;
   }
   if (std::strcmp(name, "adamw_nt") == 0) {
-    ctx->opt_adamw_nt = value != 0;
+    if (value < 0 || value > 2) return pt_fail(ctx, PT_ERR_INVALID_ARG, "adamw_nt must be 0, 1 or 2");
+    ctx->opt_adamw_nt = uint32_t(value);
     return PT_OK;
   }
   if (std::strcmp(name, "adamw_zero_grads") == 0) {

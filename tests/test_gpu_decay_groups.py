@@ -34,6 +34,7 @@ def test_masked_kernel_is_bit_exact_against_the_masked_f32_sequence(orc, dtype, 
     try:
         B.pt_ctx_set_option(st.ctx, "adamw_unroll", unroll)
         B.pt_ctx_set_option(st.ctx, "adamw_threads", threads)
+        B.pt_ctx_set_option(st.ctx, "adamw_nt", 1 if unroll != 8 else 2)     # hinted accesses too (a small state gets none by default)
         hp_b, hp_o, _ = hp_pair()
         mask = st.set_no_decay(runs=awkward_runs(S))
         assert 0 < mask.sum() < mask.size

@@ -98,6 +98,7 @@ def test_update_from_fp32_gradients_is_bit_exact_against_the_f32_sequence(orc, d
     try:
         B.pt_ctx_set_option(st.ctx, "adamw_unroll", unroll)
         B.pt_ctx_set_option(st.ctx, "adamw_zero_grads", int(zero))
+        B.pt_ctx_set_option(st.ctx, "adamw_nt", 1 if unroll != 8 else 2)     # hinted accesses too (a small state gets none by default)
         mask = st.set_no_decay(runs=[(0, 100, 5000), (1, 0, S), (2, S - 41, 41)]) if masked else None
         hp_b, hp_o, hpd = hp_pair()
         host = st.host_state()

@@ -157,12 +157,13 @@ def run_oracle_f32seq(orc, consts, st_host, dtype, no_decay=None):
 
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
-@pytest.mark.parametrize("S,C,threads", [(4096 * 3 + 40, 3, 512), (8, 2, 512), (16384 * 8, 2, 512), (4096, 1, 512),
-                                         (4096 * 3 + 40, 3, 256), (16384 * 8 + 2048, 2, 256)])
-def test_adamw_kernel_isolated_is_bit_exact_against_f32_sequence(orc, dtype, S, C, threads):
+@pytest.mark.parametrize("S,C,threads,nt", [(4096 * 3 + 40, 3, 512, 1), (8, 2, 512, 2), (16384 * 8, 2, 512, 0), (4096, 1, 512, 1),
+                                            (4096 * 3 + 40, 3, 256, 0), (16384 * 8 + 2048, 2, 256, 1)])
+def test_adamw_kernel_isolated_is_bit_exact_against_f32_sequence(orc, dtype, S, C, threads, nt):
     st = ChunkedState([S * C - 5], S, dtype=dtype)
     try:
         B.pt_ctx_set_option(st.ctx, "adamw_threads", threads)
+        B.pt_ctx_set_option(st.ctx, "adamw_nt", nt)          # with, without, or chosen by launch size: same bits
         hp_b, hp_o, hpd = hp_pair()
         host = st.host_state()
         h64 = {k: a.copy() for k, a in host.items()}
