@@ -108,3 +108,28 @@ def chunk_size_search(sizes, group_ids, min_chunk: int, span: int, step: int):
         return None
     waste, S, n_chunks = min(outcomes)
     return S, n_chunks, waste
+
+
+def execution_order(uses, n_tensors: int):
+    """The order in which the tensors are handed to the layout (Appendix B.1, first sentences of
+    "Chunk Organization and Size Search"; "Hierarchical Chunk Management for Model States"): by
+    execution order, a parameter that several layers share counted at its FIRST occurrence.
+
+    uses: the tensor indices (into the model's declaration table) in the order the forward pass
+    touches them; an index may come more than once (shared parameters, layers run twice).
+    Returns the n_tensors indices: used tensors by the position of their first use; tensors the
+    trace never touches behind them, in declaration order (reading: the paper does not say where
+    an unused parameter goes; it still needs storage).
+
+    Written as the definition: each tensor's key is where it first appears in `uses`."""
+    first = []
+    for t in range(n_tensors):
+        pos = None
+        for k, u in enumerate(uses):
+            if u == t:
+                pos = k
+                break
+        first.append(pos)
+    used = sorted((t for t in range(n_tensors) if first[t] is not None), key=lambda t: first[t])
+    unused = [t for t in range(n_tensors) if first[t] is None]
+    return used + unused

@@ -182,3 +182,35 @@ def test_search_is_the_brute_force_minimum():
                 cands.append((r[2], S, r[1]))
         waste, S, n_chunks = min(cands)
         assert got == (S, n_chunks, waste)
+
+
+# ---- execution order with shared parameters at their first occurrence (Appendix B.1)
+
+def test_execution_order_worked_by_hand():
+    # a GPT-2-like model whose modules are DECLARED head first (head tied to the token embedding):
+    #   0 head/wte   1 ln_f   2 block0.w   3 block1.w   4 wpe   5 never used
+    # forward pass: wte, wpe, block0, block1, block0 again (a layer run twice), ln_f, head (= wte again)
+    uses = [0, 4, 2, 3, 2, 1, 0]
+    assert L.execution_order(uses, 6) == [0, 4, 2, 3, 1, 5]
+    # the shared tensor counts where it is used first, not where it is used last
+    assert L.execution_order([3, 1, 3, 0], 4) == [3, 1, 0, 2]
+    # nothing shared, execution = declaration: identity; no trace at all: declaration order
+    assert L.execution_order([0, 1, 2], 3) == [0, 1, 2]
+    assert L.execution_order([], 3) == [0, 1, 2]
+    assert L.execution_order([], 0) == []
+
+
+def test_execution_order_properties_on_random_traces():
+    rng = random.Random(11)
+    for _ in range(300):
+        n = rng.randint(0, 12)
+        uses = [rng.randrange(n) for _ in range(rng.randint(0, 30))] if n else []
+        order = L.execution_order(uses, n)
+        assert sorted(order) == list(range(n))                       # a permutation: every tensor once
+        seen = []
+        for u in uses:                                               # independent formulation: walk the trace
+            if u not in seen:
+                seen.append(u)
+        assert order[:len(seen)] == seen                             # first occurrences, in trace order
+        rest = order[len(seen):]
+        assert rest == sorted(rest) and not set(rest) & set(uses)    # the unused ones behind, as declared
