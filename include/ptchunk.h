@@ -184,6 +184,14 @@ int pt_layout_grouped(const uint64_t* tensor_elems, const uint32_t* tensor_group
                       uint64_t chunk_elems, pt_segment* out, uint32_t cap, uint32_t* n_segments,
                       uint32_t* n_chunks, uint64_t* waste_elems);
 
+/* The order in which the tensors go into pt_layout_grouped (same passage: parameters are organised by
+ * execution order, and a parameter that several layers share counts at its first occurrence).
+ * uses: n_uses tensor indices (each < n_tensors) in the order the forward pass touches them; an index may
+ * repeat.  order: n_tensors entries, written with the tensors in the order of their first use, followed by
+ * the tensors the trace never names, in declaration order (the paper does not place those).
+ * PT_ERR_INVALID_ARG for an index out of range or a NULL array that is needed.  Host only. */
+int pt_layout_execution_order(const uint32_t* uses, uint32_t n_uses, uint32_t n_tensors, uint32_t* order);
+
 /* Chunk-size search of the same passage: simulates pt_layout_grouped for the candidate sizes
  * S_min, S_min + step, ... <= S_min + span, where S_min = max(largest tensor, min_chunk_elems)
  * rounded up to step_elems, and returns the size of least waste (ties: the smaller size).  The

@@ -22,7 +22,7 @@ EXPORTS = [
     "pt_layout_dense", "pt_pack_plan_create", "pt_pack_plan_destroy", "pt_chunk_pack_grads", "pt_chunk_unpack",
     "pt_chunk_grad_sqnorm", "pt_chunk_adamw_step", "pt_stream_reserve", "pt_chunk_stream_step", "pt_step_end",
     "pt_step_report_read", "pt_update_consts_read", "pt_step_override", "pt_calib_copy", "pt_ctx_set_option",
-    "pt_layout_grouped", "pt_chunk_size_search", "pt_chunk_host_adamw_step",
+    "pt_layout_grouped", "pt_chunk_size_search", "pt_layout_execution_order", "pt_chunk_host_adamw_step",
     "pt_optim_predict", "pt_optim_choose", "pt_ctx_set_no_decay", "pt_chunk_accum_grads",
     "pt_chunk_grad_sqnorm_noalloc", "pt_calib_adamw_pattern",
 ]
@@ -125,6 +125,7 @@ def lib():
         L.pt_optim_choose.argtypes = [C.POINTER(pt_optim_rates), u64, u32, u64, C.c_int, u32, C.POINTER(pt_optim_choice)]
         L.pt_layout_grouped.argtypes = [C.POINTER(u64), C.POINTER(u32), u32, u64, C.POINTER(pt_segment), u32,
                                         C.POINTER(u32), C.POINTER(u32), C.POINTER(u64)]
+        L.pt_layout_execution_order.argtypes = [C.POINTER(u32), u32, u32, C.POINTER(u32)]
         L.pt_chunk_size_search.argtypes = [C.POINTER(u64), C.POINTER(u32), u32, u64, u64, u64, C.POINTER(u64),
                                            C.POINTER(u32), C.POINTER(u64)]
         for name in EXPORTS:
@@ -315,6 +316,15 @@ def _group_array(tensor_group, n):
     if tensor_group is None:
         return None
     return (C.c_uint32 * max(n, 1))(*[PT_NO_GROUP if g is None else int(g) for g in tensor_group])
+
+
+def pt_layout_execution_order(uses, n_tensors: int):
+    """-> tensor indices by first use in the trace `uses`, unused ones behind.  Host only."""
+    n = len(uses)
+    arr = (C.c_uint32 * max(n, 1))(*[int(u) for u in uses])
+    out = (C.c_uint32 * max(int(n_tensors), 1))()
+    _check(lib().pt_layout_execution_order(arr, n, int(n_tensors), out), "pt_layout_execution_order")
+    return [int(out[i]) for i in range(int(n_tensors))]
 
 
 def pt_layout_grouped(tensor_elems, tensor_group, chunk_elems: int):

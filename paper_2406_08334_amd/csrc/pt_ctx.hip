@@ -459,6 +459,25 @@ bool place_grouped(const uint64_t* elems, const uint32_t* group, uint32_t n, uin
 
 }  // namespace
 
+extern "C" int pt_layout_execution_order(const uint32_t* uses, uint32_t n_uses, uint32_t n_tensors, uint32_t* order) {
+  if ((n_uses && !uses) || (n_tensors && !order))
+    return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_layout_execution_order: NULL pointer");
+  for (uint32_t k = 0; k < n_uses; ++k)
+    if (uses[k] >= n_tensors)
+      return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_layout_execution_order: use %u names tensor %u of %u", k, uses[k],
+                     n_tensors);
+  return pt_guarded(nullptr, "pt_layout_execution_order", [&] {
+    // one walk over the trace: a tensor takes the next place the first time it is met
+    std::vector<uint8_t> placed(n_tensors, 0);
+    uint32_t n = 0;
+    for (uint32_t k = 0; k < n_uses; ++k)
+      if (!placed[uses[k]]) { placed[uses[k]] = 1; order[n++] = uses[k]; }
+    for (uint32_t t = 0; t < n_tensors; ++t)
+      if (!placed[t]) order[n++] = t;
+    return int(PT_OK);
+  });
+}
+
 extern "C" int pt_layout_grouped(const uint64_t* tensor_elems, const uint32_t* tensor_group, uint32_t n_tensors,
                                  uint64_t chunk_elems, pt_segment* out, uint32_t cap, uint32_t* n_segments,
                                  uint32_t* n_chunks, uint64_t* waste_elems) {

@@ -45,6 +45,16 @@ int main() {
     const uint32_t gids[] = {PT_NO_GROUP, 0, 0, 1, 1, PT_NO_GROUP};
     uint32_t nseg = 0, nch = 0;
     uint64_t waste = 0;
+    {
+      const uint32_t uses[] = {2, 0, 2, 5, 0};
+      uint32_t order[6] = {9, 9, 9, 9, 9, 9};
+      EXPECT(pt_layout_execution_order(uses, 5, 6, order) == PT_OK);
+      EXPECT(order[0] == 2 && order[1] == 0 && order[2] == 5 && order[3] == 1 && order[4] == 3 && order[5] == 4);
+      EXPECT(pt_layout_execution_order(uses, 5, 5, order) == PT_ERR_INVALID_ARG);    // tensor 5 of 5
+      EXPECT(pt_layout_execution_order(nullptr, 0, 0, nullptr) == PT_OK);
+      EXPECT(pt_layout_execution_order(nullptr, 0, 2, order) == PT_OK && order[0] == 0 && order[1] == 1);
+      EXPECT(pt_layout_execution_order(nullptr, 1, 2, order) == PT_ERR_INVALID_ARG);
+    }
     EXPECT(pt_layout_grouped(sizes, gids, 6, 32, nullptr, 0, &nseg, &nch, &waste) == PT_OK);
     EXPECT(nseg == 6 && nch == 3 && waste == 3 * 32 - 53);
     std::vector<pt_segment> segs(nseg);

@@ -129,6 +129,33 @@ def test_layout_grouped_matches_the_oracle_on_random_inputs():
         assert _lib_places(sizes, gids, S) == want
 
 
+def test_execution_order_matches_the_oracle_and_feeds_the_grouped_layout():
+    """The library's first-use order against the oracle's on random traces; then end to end on a GPT-2-like table
+    declared head first with the head tied to the token embedding: ordered by the forward trace, the embedding
+    leads, the blocks follow whole, and the layout of the reordered table equals the oracle's."""
+    import random
+    from oracle import layout as OL
+    rng = random.Random(23)
+    for _ in range(300):
+        n = rng.randint(0, 14)
+        uses = [rng.randrange(n) for _ in range(rng.randint(0, 40))] if n else []
+        assert B.pt_layout_execution_order(uses, n) == OL.execution_order(uses, n)
+    with pytest.raises(B.PtError):
+        B.pt_layout_execution_order([0, 3], 3)                      # names a tensor that does not exist
+    # declaration: 0 wte (tied head), 1 ln_f.g, 2 ln_f.b, then two blocks of three tensors, 9 wpe
+    sizes = [4096, 64, 64, 640, 72, 640, 640, 72, 640, 512]
+    gids = [None, None, None, 0, 0, 0, 1, 1, 1, None]
+    trace = [0, 9, 3, 4, 5, 6, 7, 8, 1, 2, 0]                        # embeddings, blocks, final norm, head = wte again
+    order = B.pt_layout_execution_order(trace, len(sizes))
+    assert order == [0, 9, 3, 4, 5, 6, 7, 8, 1, 2]
+    o_sizes, o_gids = [sizes[t] for t in order], [gids[t] for t in order]
+    S = 4096
+    place, n_chunks, waste = _lib_places(o_sizes, o_gids, S)
+    assert (place, n_chunks, waste) == OL.layout_grouped(o_sizes, o_gids, S)
+    assert place[0] == (0, 0) and place[1][0] == 1                   # the shared embedding alone in chunk 0, wpe opens chunk 1
+    assert len({place[k][0] for k in (2, 3, 4)}) == 1 and len({place[k][0] for k in (5, 6, 7)}) == 1   # blocks whole
+
+
 def test_chunk_size_search_matches_the_oracle_and_the_papers_table():
     import random
     from oracle import layout as OL
