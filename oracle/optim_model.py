@@ -11,15 +11,26 @@ STREAM, HOST = 0, 1
 
 
 def predict(rates: dict, S: int, C: int, n_persist: int, mode: int):
+    """(t_gpu, t_other, t_step).  The resident part and the other part run side by side and the longer one
+    decides (the paper's max), except that the other part cannot start before the gradient norm is final:
+    the share `gpu_serial_share` of the resident part (the gradient pack and its reduction, which come
+    before the norm) is served first, the rest of the resident part runs beside the other part.  With
+    global-norm clipping no update - on the GPU, through the chunk buffers or on the host - may read a
+    gradient before that.  (Reading: the paper overlaps its CPU update with the backward pass and has no
+    clipping; share 0 gives its plain max.)"""
     res, rest = S * n_persist, S * (C - n_persist)
     t_gpu = max(0.0, rates["gpu_s_fixed"] + rates["gpu_s_per_elem"] * res) if res else 0.0
     if mode == STREAM:
         t_other = max(0.0, rates["link_s_fixed"] + rates["link_s_per_elem"] * rest) if rest else 0.0
     else:
         t_other = max(0.0, rates["host_s_fixed"] + rates["host_s_per_elem"] * rest) if rest else 0.0
-    t = max(t_gpu, t_other)
-    if mode == STREAM and res and rest:
-        t += rates["stream_contention"] * min(t_gpu, t_other)
+    if not rest:
+        return t_gpu, t_other, t_gpu
+    t_first = rates.get("gpu_serial_share", 0.0) * t_gpu
+    t_beside = t_gpu - t_first
+    t = t_first + max(t_beside, t_other)
+    if mode == STREAM and res:
+        t += rates["stream_contention"] * min(t_beside, t_other)
     return t_gpu, t_other, t
 
 

@@ -27,6 +27,32 @@ def test_oracle_closed_forms():
     assert t == max(tg, to)
     tg, to, t = OM.predict(RATES, S, C, 100, OM.STREAM)
     assert t == max(tg, to) + 0.5 * min(tg, to)
+    # the part of the resident work that comes before the norm (share s) is served first, the rest runs beside
+    # the other part: host part longer -> s*tg + to; resident part longer -> tg; s = 0 -> the plain max
+    for s_ in (0.0, 0.125, 0.5, 1.0):
+        r = dict(RATES, gpu_serial_share=s_)
+        tg, to, t = OM.predict(r, S, C, 100, OM.HOST)                 # 100 resident, 94 on the host: host part longer
+        assert to > tg and t == s_ * tg + to
+        tg, to, t = OM.predict(r, S, C, 190, OM.HOST)                 # 4 on the host: resident part longer ...
+        assert tg > to
+        if (1 - s_) * tg > to:
+            assert abs(t - tg) <= 1e-18                               # ... and still longer without its serial share
+        else:
+            assert abs(t - (s_ * tg + to)) <= 1e-18
+        assert OM.predict(r, S, C, C, OM.HOST)[2] == OM.predict(RATES, S, C, C, OM.HOST)[2]    # all resident: no share
+        assert OM.predict(r, S, C, 0, OM.STREAM)[2] == OM.predict(RATES, S, C, 0, OM.STREAM)[2]  # nothing resident
+        tg, to, t = OM.predict(r, S, C, 100, OM.STREAM)
+        assert abs(t - (s_ * tg + max((1 - s_) * tg, to) + 0.5 * min((1 - s_) * tg, to))) <= 1e-15
+    prev = 0.0
+    for s_ in (0.0, 0.1, 0.3, 0.9):                                   # more serial work never makes a step shorter
+        t = OM.predict(dict(RATES, gpu_serial_share=s_), S, C, 150, OM.HOST)[2]
+        assert t >= prev
+        prev = t
+    # balanced point with a serial share: (1-s) * gpu rate * resident elements = host rate * host elements
+    r = dict(RATES, gpu_s_fixed=0.0, host_s_fixed=0.0, gpu_serial_share=0.25)
+    n, t, need, buffers = OM.choose(r, S, 1000, 1 << 62, OM.HOST, 0)
+    g_, h_ = 0.75 * r["gpu_s_per_elem"], r["host_s_per_elem"]
+    assert abs((1000 - n) / 1000 - g_ / (g_ + h_)) <= 2e-3
     # balanced point of the host mode: with zero fixed costs the best split makes both parts equal,
     # n*/C = host rate / (host rate + gpu rate) of the ELEMENTS go to the host
     r = dict(RATES, gpu_s_fixed=0.0, host_s_fixed=0.0)
