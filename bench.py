@@ -591,7 +591,7 @@ def fit_optim_model(B, np, torch, ctx, hp, stream, S, C, n_persist, n_host, plan
             plans_by_n[n] = B.pt_pack_plan_create(ctx, [s_ for s_ in res_segs if s_.chunk < n])
         return plans_by_n[n]
 
-    def run(n_res, n_h, mode, k=3):
+    def run(n_res, n_h, mode, k=3, update=True):
         pl = plan_for(n_res) if n_res else None
 
         def once():
@@ -600,8 +600,10 @@ def fit_optim_model(B, np, torch, ctx, hp, stream, S, C, n_persist, n_host, plan
             B.pt_chunk_grad_sqnorm(ctx, None, 0, C, B.PT_FINALIZE_CARRY, stream)
             if n_h and mode == B.PT_OPTIM_STREAM:
                 B.pt_chunk_stream_step(ctx, hp, n_persist, n_h, h_g[:n_h], h_w[:n_h], h_m[:n_h], h_v[:n_h], h_p[:n_h], stream)
-            if n_res:
+            if n_res and update:
                 B.pt_chunk_adamw_step(ctx, hp, 0, n_res, r_g[:n_res], r_w[:n_res], r_m[:n_res], r_v[:n_res], r_p[:n_res], stream)
+            if not update:
+                B.pt_step_report_read(ctx, stream)      # a step that ends at the norm: the scalar kernel runs here
             if n_h and mode == B.PT_OPTIM_HOST:
                 B.pt_chunk_host_adamw_step(ctx, hp, n_persist, n_h, h_g[:n_h], h_w[:n_h], h_m[:n_h], h_v[:n_h], h_p[:n_h],
                                            host_threads, stream)
@@ -626,9 +628,12 @@ def fit_optim_model(B, np, torch, ctx, hp, stream, S, C, n_persist, n_host, plan
     l_fix, l_per = fit([(n * S, run(0, n, B.PT_OPTIM_STREAM, k=2)) for n in hs])
     h_fix, h_per = fit([(n * S, run(0, n, B.PT_OPTIM_HOST)) for n in hs])
     tg_, tl_ = g_fix + g_per * n_persist * S, l_fix + l_per * hs[1] * S
+    # the resident work that comes before the norm is final (pack + reduction): the same step without its update
+    share = min(1.0, run(n_persist, 0, B.PT_OPTIM_HOST, update=False) / tg_)
     t_mix = run(n_persist, hs[1], B.PT_OPTIM_STREAM, k=2)
-    cont = max(0.0, (t_mix - max(tg_, tl_)) / min(tg_, tl_))
-    rates = B.pt_optim_rates(g_fix, g_per, l_fix, l_per, h_fix, h_per, cont)
+    beside_ = (1.0 - share) * tg_
+    cont = max(0.0, (t_mix - share * tg_ - max(beside_, tl_)) / min(beside_, tl_))
+    rates = B.pt_optim_rates(g_fix, g_per, l_fix, l_per, h_fix, h_per, cont, share)
     held_out = [(n_persist // 2, n_host // 2, B.PT_OPTIM_STREAM), (n_persist, n_host, B.PT_OPTIM_STREAM),
                 (3 * n_persist // 4, n_host // 4, B.PT_OPTIM_STREAM),
                 (n_persist, n_host, B.PT_OPTIM_HOST), (n_persist // 2, n_host // 2, B.PT_OPTIM_HOST),
@@ -655,7 +660,8 @@ def fit_optim_model(B, np, torch, ctx, hp, stream, S, C, n_persist, n_host, plan
         if n != n_persist:
             B.pt_pack_plan_destroy(pl)
     return {"rates": {"gpu_s_fixed": g_fix, "gpu_s_per_elem": g_per, "link_s_fixed": l_fix, "link_s_per_elem": l_per,
-                      "host_s_fixed": h_fix, "host_s_per_elem": h_per, "stream_contention": round(cont, 3)},
+                      "host_s_fixed": h_fix, "host_s_per_elem": h_per, "stream_contention": round(cont, 3),
+                      "gpu_serial_share": round(share, 4)},
             "fit_sizes_chunks": {"gpu": gs, "other": hs}, "held_out": rows_,
             "max_abs_error_pct": max(abs(r_["error_pct"]) for r_ in rows_),
             "chooser_for_%d_chunks" % total: choices}

@@ -380,15 +380,19 @@ int pt_step_override(pt_ctx* ctx, float grad_mult, int32_t found_inf, void* stre
  *   resident part   t = gpu_s_fixed  + gpu_s_per_elem  * n_persist * chunk_elems      (pack + update)
  *   streamed part   t = link_s_fixed + link_s_per_elem * rest                         (PT_OPTIM_STREAM)
  *   host-side part  t = host_s_fixed + host_s_per_elem * rest                         (PT_OPTIM_HOST)
- *   step            t = max(resident, other) [+ stream_contention * min(resident, other) when streaming:
+ *   step            t = first + max(beside, other) [+ stream_contention * min(beside, other) when streaming:
  *                       the slot kernels and DMA engines share HBM with the resident update]
- * A part over zero elements costs nothing. */
+ *                   where first = gpu_serial_share * resident is the resident work that comes before the gradient
+ *                   norm is final (pack and reduction) and beside = resident - first: under global-norm clipping
+ *                   the other part cannot start earlier.  gpu_serial_share = 0 gives the paper's plain max.
+ * A part over zero elements costs nothing; with every chunk resident the step is the resident part. */
 typedef enum { PT_OPTIM_STREAM = 0, PT_OPTIM_HOST = 1 } pt_optim_mode;
 typedef struct {
   double gpu_s_fixed, gpu_s_per_elem;
   double link_s_fixed, link_s_per_elem;
   double host_s_fixed, host_s_per_elem;
   double stream_contention;
+  double gpu_serial_share;   /* in [0, 1] */
 } pt_optim_rates;
 typedef struct {
   uint32_t n_persist;  /* resident chunks: the first n_persist of the model (prefix rule)   */

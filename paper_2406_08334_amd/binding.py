@@ -56,7 +56,7 @@ class pt_update_consts(C.Structure):
 class pt_optim_rates(C.Structure):
     _fields_ = [("gpu_s_fixed", C.c_double), ("gpu_s_per_elem", C.c_double), ("link_s_fixed", C.c_double),
                 ("link_s_per_elem", C.c_double), ("host_s_fixed", C.c_double), ("host_s_per_elem", C.c_double),
-                ("stream_contention", C.c_double)]
+                ("stream_contention", C.c_double), ("gpu_serial_share", C.c_double)]
 
 
 class pt_optim_choice(C.Structure):

@@ -26,9 +26,14 @@ int predict(const pt_optim_rates* r, uint64_t S, uint32_t C, uint32_t n_persist,
   double to = 0.0;
   if (mode == PT_OPTIM_STREAM) to = lin(r->link_s_fixed, r->link_s_per_elem, rest);
   else to = lin(r->host_s_fixed, r->host_s_per_elem, rest);
-  // the two parts run side by side; a streamed part also shares the GPU with the resident one
-  double ts = tg > to ? tg : to;
-  if (mode == PT_OPTIM_STREAM && rest > 0 && res > 0) ts += r->stream_contention * (tg < to ? tg : to);
+  // The resident work that precedes the norm comes first; the rest of it and the other part run side by
+  // side; a streamed part also shares the GPU with the resident one.
+  double ts = tg;
+  if (rest > 0) {
+    const double first = r->gpu_serial_share * tg, beside = tg - first;
+    ts = first + (beside > to ? beside : to);
+    if (mode == PT_OPTIM_STREAM && res > 0) ts += r->stream_contention * (beside < to ? beside : to);
+  }
   if (t_gpu) *t_gpu = tg;
   if (t_other) *t_other = to;
   if (t_step) *t_step = ts;
@@ -44,6 +49,8 @@ extern "C" int pt_optim_predict(const pt_optim_rates* rates, uint64_t chunk_elem
     return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_optim_predict: chunk_elems > 0 and n_persist <= n_chunks required");
   if (mode != PT_OPTIM_STREAM && mode != PT_OPTIM_HOST)
     return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_optim_predict: mode must be PT_OPTIM_STREAM or PT_OPTIM_HOST");
+  if (!(rates->gpu_serial_share >= 0.0) || !(rates->gpu_serial_share <= 1.0))
+    return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_optim_predict: gpu_serial_share must be in [0, 1]");
   return predict(rates, chunk_elems, n_chunks, n_persist, mode, t_gpu, t_other, t_step);
 }
 
@@ -54,6 +61,8 @@ extern "C" int pt_optim_choose(const pt_optim_rates* rates, uint64_t chunk_elems
     return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_optim_choose: chunk_elems and n_chunks must be > 0");
   if (mode != PT_OPTIM_STREAM && mode != PT_OPTIM_HOST)
     return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_optim_choose: mode must be PT_OPTIM_STREAM or PT_OPTIM_HOST");
+  if (!(rates->gpu_serial_share >= 0.0) || !(rates->gpu_serial_share <= 1.0))
+    return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_optim_choose: gpu_serial_share must be in [0, 1]");
   if (mode == PT_OPTIM_STREAM && (n_slots < 2 || n_slots > PT_MAX_SLOTS))
     return pt_fail(nullptr, PT_ERR_INVALID_ARG, "pt_optim_choose: n_slots must be in [2, %u] for the streamed mode", PT_MAX_SLOTS);
   const uint64_t per_chunk = 16 * chunk_elems;

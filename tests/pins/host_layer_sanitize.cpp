@@ -72,7 +72,7 @@ int main() {
   }
   // ---- cost model and chooser
   {
-    pt_optim_rates r{1e-3, 5e-12, 2e-3, 3e-10, 1e-4, 7e-11, 0.3};
+    pt_optim_rates r{1e-3, 5e-12, 2e-3, 3e-10, 1e-4, 7e-11, 0.3, 0.125};
     double tg = 0, to = 0, ts = 0;
     EXPECT(pt_optim_predict(&r, 1 << 20, 10, 10, PT_OPTIM_STREAM, &tg, &to, &ts) == PT_OK && to == 0 && ts == tg);
     EXPECT(pt_optim_predict(&r, 1 << 20, 10, 0, PT_OPTIM_HOST, &tg, &to, &ts) == PT_OK && tg == 0 && ts == to);

@@ -9,13 +9,13 @@ from oracle import optim_model as OM
 from paper_2406_08334_amd import binding as B
 
 RATES = dict(gpu_s_fixed=2e-5, gpu_s_per_elem=5.1e-12, link_s_fixed=4e-3, link_s_per_elem=3.1e-10,
-             host_s_fixed=1e-4, host_s_per_elem=7.3e-11, stream_contention=0.5)
+             host_s_fixed=1e-4, host_s_per_elem=7.3e-11, stream_contention=0.5, gpu_serial_share=0.0)
 S, C = 1 << 26, 194
 
 
 def lib_rates(r):
     return B.pt_optim_rates(*[r[k] for k in ("gpu_s_fixed", "gpu_s_per_elem", "link_s_fixed", "link_s_per_elem",
-                                              "host_s_fixed", "host_s_per_elem", "stream_contention")])
+                                              "host_s_fixed", "host_s_per_elem", "stream_contention", "gpu_serial_share")])
 
 
 def test_oracle_closed_forms():
@@ -74,6 +74,7 @@ def test_library_matches_the_oracle():
     for _ in range(300):
         r = {k: v * rng.uniform(0.2, 5.0) for k, v in RATES.items()}
         r["stream_contention"] = rng.uniform(0.0, 1.0)
+        r["gpu_serial_share"] = rng.choice([0.0, 1.0, rng.uniform(0.0, 1.0)])
         s = 8 * rng.randint(1, 1 << 20)
         c = rng.randint(1, 300)
         mode = rng.choice([OM.STREAM, OM.HOST])
@@ -93,6 +94,9 @@ def test_library_matches_the_oracle():
         assert abs(ch.t_step - want[1]) <= 1e-12 * want[1]
     neg = dict(RATES, gpu_s_fixed=-1.0)                            # a fitted intercept below zero never gives a negative time
     assert B.pt_optim_predict(lib_rates(neg), S, C, 1, OM.HOST)[0] == 0.0 == OM.predict(neg, S, C, 1, OM.HOST)[0]
+    for bad in (-0.1, 1.5, float("nan")):
+        with pytest.raises(B.PtError):
+            B.pt_optim_predict(lib_rates(dict(RATES, gpu_serial_share=bad)), S, C, 1, OM.HOST)
     with pytest.raises(B.PtError):
         B.pt_optim_predict(lib_rates(RATES), S, C, C + 1, OM.HOST)
     with pytest.raises(B.PtError):
