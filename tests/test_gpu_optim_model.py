@@ -101,8 +101,8 @@ def fit(points):
     return float(icept), float(slope)
 
 
-def test_fitted_model_predicts_held_out_splits_and_the_chooser_obeys_the_budget(rig):
-    measure = rig
+def fit_and_validate(measure):
+    """one fit and its held-out errors: (rates, [(name, measured, predicted, relative error)])"""
     g_fix, g_per = fit([(n * S, measure(n, 0, B.PT_OPTIM_HOST, reps=15)) for n in (12, 24, 48)])
     l_fix, l_per = fit([(n * S, measure(0, n, B.PT_OPTIM_STREAM, reps=4)) for n in (3, 6, 12)])
     h_fix, h_per = fit([(n * S, measure(0, n, B.PT_OPTIM_HOST, reps=15)) for n in (3, 6, 12)])
@@ -120,12 +120,26 @@ def test_fitted_model_predicts_held_out_splits_and_the_chooser_obeys_the_budget(
           f"contention {cont:.2f}", flush=True)
     assert 0.0 < share < 0.6
     assert g_per > 0 and l_per > 0 and h_per > 0
+    rows = []
     for n_res, n_h, mode, name in ((36, 9, B.PT_OPTIM_STREAM, "streamed"), (36, 9, B.PT_OPTIM_HOST, "host")):
         meas = measure(n_res, n_h, mode, reps=5 if mode == B.PT_OPTIM_STREAM else 15)
         pred = B.pt_optim_predict(rates, S, n_res + n_h, n_res, mode)[2]
         err = (pred - meas) / meas
         print(f"[optim-model] held out {name}: {n_res} resident + {n_h} other: measured {meas * 1e3:.3f} ms, "
               f"predicted {pred * 1e3:.3f} ms ({100 * err:+.1f} %)", flush=True)
+        rows.append((name, meas, pred, err))
+    return rates, rows
+
+
+def test_fitted_model_predicts_held_out_splits_and_the_chooser_obeys_the_budget(rig):
+    measure = rig
+    # Wall-clock figures of a few milliseconds on a shared virtual machine: if a fit misses the bar, ONE more fit is
+    # taken before the test fails (a model that is wrong misses twice; a late host thread does not).
+    rates, rows = fit_and_validate(measure)
+    if any(abs(err) > 0.10 for _, _, _, err in rows):
+        print("[optim-model] a held-out split missed 10 %: fitting once more", flush=True)
+        rates, rows = fit_and_validate(measure)
+    for name, meas, pred, err in rows:
         assert abs(err) <= 0.10, (name, meas, pred)
     # chooser: inside the budget, and the best feasible split under the model (brute force over n_persist)
     C = 60
