@@ -220,7 +220,9 @@ int pt_pack_plan_destroy(pt_pack_plan* plan);
  * NaN", left in the context for pt_chunk_grad_sqnorm(..., NULL, ...).
  * Words of the chunk that no segment covers (padding) are not written.
  * grad_chunks: host array of ctx.n_chunks device pointers (entries of chunks the
- * plan does not touch may be NULL). */
+ * plan does not touch may be NULL).
+ * PT_ERR_STATE if another plan has packed into one of this plan's chunks since the last
+ * pt_step_end (the chunk's sum would be this plan's share only): one plan per chunk and step. */
 int pt_chunk_pack_grads(pt_ctx* ctx, const pt_pack_plan* plan, void* const* grad_chunks, void* stream);
 
 /* Gradient accumulation over micro-batches (a variant; needs option "grad_fp32").  For every
@@ -258,8 +260,9 @@ int pt_chunk_unpack(pt_ctx* ctx, const pt_pack_plan* plan, const void* const* ch
  *   PT_FINALIZE_CARRY (2): chunks without a value from this step keep their old one (a
  *     gradient chunk that was reduced before it was offloaded and has not changed since).
  *   A chunk keeps the value of the LAST call that reduced it: pack all of a chunk's
- *   gradients with one plan per step (two plans that share a chunk leave the second
- *   plan's partial only), or recompute the chunk afterwards.
+ *   gradients with one plan per step.  pt_chunk_pack_grads refuses (PT_ERR_STATE) a plan that
+ *   touches a chunk another plan has packed in this step - the first plan's share would drop
+ *   out of the norm - unless the chunk was recomputed in between.
  *   PT_ERR_STATE while a streamed update is still open (pt_step_end closes it). */
 #define PT_FINALIZE_STRICT 1
 #define PT_FINALIZE_CARRY 2

@@ -75,6 +75,7 @@ struct pt_pack_plan {
   double* d_tile_sq = nullptr;
   uint32_t* d_tile_flag = nullptr;
   uint64_t total_elems = 0;
+  uint64_t id = 0;                         // never reused within a context (a destroyed plan's address may be)
   std::vector<uint32_t> touched;           // chunks that own at least one tile
 };
 
@@ -117,6 +118,8 @@ struct pt_ctx {
   uint32_t* d_norm_flag = nullptr;      // [C * norm_blocks]
 
   // host-side step bookkeeping
+  std::vector<uint64_t> chunk_packed_by;   // [C] id of the pack plan whose partial sum is the chunk's value in this step, 0 = none
+  uint64_t plan_ids = 0;
   std::vector<uint8_t> chunk_fresh;     // [C] 1 = the chunk's sum of squares was taken in this step (since pt_step_end)
   bool norm_finalized = false;
   bool prepared = false;

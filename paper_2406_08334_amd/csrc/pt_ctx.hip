@@ -116,6 +116,7 @@ static int ctx_alloc(pt_ctx* ctx, const pt_scaler_cfg* sc) {
   PT_HIP(ctx, hipMemset(ctx->d_table, 0, tab_bytes));
   ctx->h_table.assign(size_t(N_ROWS) * ctx->table_cols, 0);
   ctx->chunk_fresh.assign(ctx->C, 0);
+  ctx->chunk_packed_by.assign(ctx->C, 0);
   PT_HIP(ctx, hipMalloc(&ctx->d_chunk_sq, ctx->C * sizeof(double)));
   PT_HIP(ctx, hipMemset(ctx->d_chunk_sq, 0, ctx->C * sizeof(double)));
   PT_HIP(ctx, hipMalloc(&ctx->d_chunk_flag, ctx->C * sizeof(uint32_t)));
@@ -315,6 +316,7 @@ extern "C" int pt_step_end(pt_ctx* ctx, void* stream) {
   ctx->norm_finalized = false;
   ctx->prepared = false;
   std::fill(ctx->chunk_fresh.begin(), ctx->chunk_fresh.end(), uint8_t(0));   // the next step needs new partial sums
+  std::fill(ctx->chunk_packed_by.begin(), ctx->chunk_packed_by.end(), uint64_t(0));
   return PT_OK;
 }
 

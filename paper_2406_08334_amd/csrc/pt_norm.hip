@@ -356,7 +356,8 @@ extern "C" int pt_chunk_grad_sqnorm(pt_ctx* ctx, const void* const* grad_chunks,
     int rc2 = pt_launch_chunk_reduce(ctx, ctx->d_norm_part, ctx->d_norm_flag, nullptr, first_chunk, n_chunks,
                                      ctx->norm_blocks, st, nullptr, 0, n_chunks);
     if (rc2 != PT_OK) return rc2;
-    for (uint32_t c = first_chunk; c < first_chunk + n_chunks; ++c) ctx->chunk_fresh[c] = 1;
+    // a recompute covers the whole chunk: whatever plan packed it, its value is complete now
+    for (uint32_t c = first_chunk; c < first_chunk + n_chunks; ++c) { ctx->chunk_fresh[c] = 1; ctx->chunk_packed_by[c] = 0; }
   }
   if (finalize) {
     if (ctx->stream_pending)

@@ -218,6 +218,7 @@ static int plan_create(pt_ctx* ctx, const pt_segment* segs, uint32_t n_segs, pt_
   if (!p) return pt_fail(ctx, PT_ERR_NOMEM, "pt_pack_plan_create: out of host memory");
   std::unique_ptr<pt_pack_plan> hold(p);            // freed on every early return and on an exception
   p->ctx = ctx; p->n_tiles = uint32_t(tiles.size()); p->total_elems = total;
+  p->id = ++ctx->plan_ids;
   for (uint32_t c = 0; c < ctx->C; ++c)
     if (begin[c + 1] > begin[c]) p->touched.push_back(c);
   auto bail = [&](hipError_t e, const char* what) {
@@ -246,6 +247,9 @@ extern "C" int pt_pack_plan_destroy(pt_pack_plan* plan) {
   if (plan->ctx && plan->ctx->pend_reduce.active && plan->ctx->pend_reduce.plan == plan)
     (void)pt_flush_pending(plan->ctx, plan->ctx->pend_reduce.stream);
   (void)hipDeviceSynchronize();
+  if (plan->ctx)      // a plan that no longer exists does not stand in another plan's way
+    for (uint32_t c : plan->touched)
+      if (plan->ctx->chunk_packed_by[c] == plan->id) plan->ctx->chunk_packed_by[c] = 0;
   plan_free(plan);
   delete plan;
   return PT_OK;
@@ -265,6 +269,15 @@ static int run_pack(pt_ctx* ctx, const pt_pack_plan* plan, const void* const* ch
   const uint64_t* h = ctx->h_table.data() + size_t(row) * ctx->table_cols;
   for (uint32_t c : plan->touched)
     if (!h[c]) return pt_fail(ctx, PT_ERR_INVALID_ARG, "%s: chunk %u is used by the plan but its pointer is NULL", who, c);
+  if (DIR == 0) {
+    // A chunk's sum of squares is the partial of the LAST plan that packed into it: a second plan on the same
+    // chunk in one step would silently drop the first plan's share from the norm.
+    for (uint32_t c : plan->touched)
+      if (ctx->chunk_packed_by[c] && ctx->chunk_packed_by[c] != plan->id)
+        return pt_fail(ctx, PT_ERR_STATE, "%s: chunk %u already holds the gradients of another plan of this step; its sum of "
+                       "squares would be replaced, not added to - pack a chunk with one plan per step (or recompute the "
+                       "norm from the chunks with pt_chunk_grad_sqnorm(grad_chunks, ...) before packing again)", who, c);
+  }
   dim3 grid(plan->n_tiles);
   // The inverse copy has no arithmetic to pace it; measured on MI355X it runs 15 % faster with three
   // workgroups per compute unit than with the eight that fit (4.24 against 4.96 ms for 6.7e9 elements).
@@ -281,7 +294,7 @@ static int run_pack(pt_ctx* ctx, const pt_pack_plan* plan, const void* const* ch
     rc = pt_launch_chunk_reduce(ctx, plan->d_tile_sq, plan->d_tile_flag, plan->d_chunk_tile_begin, 0, ctx->C, 0, st, plan,
                                 plan->n_tiles, uint32_t(plan->touched.size()));
     if (rc != PT_OK) return rc;
-    for (uint32_t c : plan->touched) ctx->chunk_fresh[c] = 1;
+    for (uint32_t c : plan->touched) { ctx->chunk_fresh[c] = 1; ctx->chunk_packed_by[c] = plan->id; }
   }
   return PT_OK;
 }

@@ -535,9 +535,23 @@ def test_error_paths_return_codes_and_leave_the_context_usable():
         with pytest.raises(B.PtError) as e:
             B.pt_chunk_pack_grads(st.ctx, st.plan, [None, None])
         assert e.value.status == B.PT_ERR_INVALID_ARG
+        # a second plan on a chunk that this step's plan has packed would replace its share of the norm: refused
+        other = B.pt_pack_plan_create(st.ctx, [B.pt_segment(st.grad_src.data_ptr(), 0, 64, 0, 0, 0)])
+        with pytest.raises(B.PtError) as e:
+            B.pt_chunk_pack_grads(st.ctx, other, st.rows(st.g16))
+        assert e.value.status == B.PT_ERR_STATE and "another plan" in str(e.value)
+        st.pack()                                                # the step's own plan may pack again
+        st.norm()
         # after all that the step still completes normally
         st.adamw(hp_b); st.end()
         assert st.report().step == 1
+        B.pt_chunk_pack_grads(st.ctx, other, st.rows(st.g16))    # a new step: any one plan per chunk
+        with pytest.raises(B.PtError) as e:
+            st.pack()
+        assert e.value.status == B.PT_ERR_STATE
+        B.pt_pack_plan_destroy(other)                            # ... and a plan that is gone stands in nobody's way
+        st.pack(); st.norm(); st.adamw(hp_b); st.end()
+        assert st.report().step == 2
     finally:
         st.close()
 
