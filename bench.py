@@ -791,8 +791,13 @@ def main() -> int:
         t_o = time.time()
         for name in OTHER_CONFIGS:
             extra = ["--no-cpu-baseline"] if args.no_cpu_baseline else []
-            res = subprocess.run([sys.executable, os.path.abspath(__file__), "--one-config", name] + extra,
-                                 stdout=subprocess.PIPE, text=True)
+            try:
+                res = subprocess.run([sys.executable, os.path.abspath(__file__), "--one-config", name] + extra,
+                                     stdout=subprocess.PIPE, text=True, timeout=420)
+            except subprocess.TimeoutExpired:
+                others[name] = {"error": "child process did not finish within 420 s and was stopped"}
+                log(f"[bench] configuration {name} did not finish within 420 s")
+                continue
             lines = [l for l in res.stdout.splitlines() if l.startswith("{")]
             if res.returncode != 0 or not lines:
                 others[name] = {"error": f"child process exited with code {res.returncode}"}
