@@ -411,6 +411,8 @@ def run_split(steps, warmup, slots=3, host_chunks=0, host_update=False, host_thr
     t0 = time.time()
     ctx = B.pt_ctx_create(B.PT_BF16, S, C, None)
     B.pt_stream_reserve(ctx, slots)
+    stream_status = B.pt_stream_status(ctx)
+    log(f"[bench] copy streams: {stream_status}")
     n_res = n_persist * S
     g16, p16, w, m, v = spread_arenas(
         [((n_persist, S), torch.bfloat16), ((n_persist, S), torch.bfloat16), ((n_persist, S), torch.float32),
@@ -565,6 +567,7 @@ def run_split(steps, warmup, slots=3, host_chunks=0, host_update=False, host_thr
         "link_utilisation_vs_one_direction_rate": round(per_dir / one_dir, 4),
         "link_utilisation_vs_bare_both_directions": round(per_dir / bare["each_direction_when_both"], 4),
         "ms_resident_only": round(1e3 * t_res, 2), "ms_streamed_only": round(1e3 * t_str, 2),
+        "copy_streams_self_test": stream_status,
         "overlap_ratio_step_over_max": round(t_step / max(t_res, t_str), 4),
         "resident_GBps": round((PACK_BYTES_PER_ELEM + ADAMW_BYTES_PER_ELEM) * n_res / t_res / 1e9, 1),
         "step_report": {"norm": rep.norm, "found_inf": rep.found_inf, "step": rep.step},

@@ -144,6 +144,10 @@ int pt_ctx_set_no_decay(pt_ctx* ctx, const pt_segment* segs, uint32_t n_segs);
  *   "adamw_nt"      non-temporal hints on the update's loads and stores: 1 = always, 0 = never, 2 = the library
  *                   chooses by launch size (default): none while the launch's state fits the 256 MB Infinity Cache
  *   "pack_tile_elems"  elements one workgroup of pack/unpack moves; read by pt_pack_plan_create
+ *   "stream_test_reject"  for tests of pt_stream_reserve: its trial of the copy streams rejects that many
+ *                   stream pairs (0..5) whatever it measures, so that the replacement runs
+ *   "stream_test_unhealthy"  for tests: 1 = the next look at a finished streamed step finds it serialised
+ *                   whatever it measured, so that the replacement of the side streams runs
  * Gradient storage (variants of the path; the paper's gradients are the 16-bit array):
  *   "grad_fp32"     1 = the gradient chunks of this context hold fp32 (micro-batches accumulated
  *                   by pt_chunk_accum_grads): every `grad` / `h_grad` argument of the norm, the
@@ -316,8 +320,19 @@ int pt_chunk_adamw_step(pt_ctx* ctx, const pt_hparams* hp, uint32_t first_chunk,
 
 /* Device chunk buffers for the streamed path (paper: pre-allocated chunk buffers
  * for non-persistent chunks).  Allocates n_slots buffers of 16 bytes x chunk_elems,
- * three side streams and the events.  n_slots >= 2.  Not a hot call. */
+ * three side streams and the events.  n_slots >= 2.  Not a hot call.
+ * With chunk buffers of 32 MiB or more it also makes the first copies of the upload and the offload stream
+ * itself, side by side (a stream keeps the copy engine of its first copy, and two streams that took the same
+ * one carry one direction of the link at a time), then measures one copy up, one down and both at once
+ * through the first buffer and a pinned scratch that is freed again; a pair that does not overlap is replaced,
+ * up to five times.  Skipped when the scratch (at most 128 MiB, kept until the context goes) cannot be pinned. */
 int pt_stream_reserve(pt_ctx* ctx, uint32_t n_slots);
+
+/* Outcome of that test: duplex_tested 0 = not run; duplex_ok 1 = upload and offload overlapped; attempts =
+ * stream pairs tried (1 = the first pair overlapped); rebuilds = times pt_chunk_stream_step has replaced the
+ * side streams since (see there).  Any pointer may be NULL.  Host only. */
+int pt_stream_status(const pt_ctx* ctx, int32_t* duplex_tested, int32_t* duplex_ok, int32_t* attempts,
+                     int32_t* rebuilds);
 
 /* Update of host-resident ("non-persistent") chunks through the chunk buffers
  * (paper: non-persistent chunks are offloaded to CPU memory and moved over the
@@ -339,7 +354,11 @@ int pt_stream_reserve(pt_ctx* ctx, uint32_t n_slots);
  * Requires pt_stream_reserve and a finalized norm in this step.
  * The upload and offload streams want hardware queues of their own: in a process that holds many other
  * streams (HIP maps streams onto GPU_MAX_HW_QUEUES hardware queues, 4 by default) the two directions can
- * end up behind each other, and the link then carries one direction at a time. */
+ * end up behind each other, and the link then carries one direction at a time.  pt_stream_reserve checks
+ * single copies for that; and each call here first reads two timed events that bracketed the previous
+ * streamed step (if they are done: it never waits): a step that moved less than 0.65 of the link's
+ * one-direction rate had its directions behind each other, and the call then replaces the three side
+ * streams by new ones before it enqueues anything (at most four times per context; pt_stream_status). */
 int pt_chunk_stream_step(pt_ctx* ctx, const pt_hparams* hp, uint32_t first_chunk, uint32_t n_chunks,
                          const void* const* h_grad, float* const* h_master, float* const* h_m,
                          float* const* h_v, void* const* h_param16, void* stream);

@@ -24,7 +24,7 @@ EXPORTS = [
     "pt_step_report_read", "pt_update_consts_read", "pt_step_override", "pt_calib_copy", "pt_ctx_set_option",
     "pt_layout_grouped", "pt_chunk_size_search", "pt_layout_execution_order", "pt_chunk_host_adamw_step",
     "pt_optim_predict", "pt_optim_choose", "pt_ctx_set_no_decay", "pt_chunk_accum_grads",
-    "pt_chunk_grad_sqnorm_noalloc", "pt_calib_adamw_pattern",
+    "pt_chunk_grad_sqnorm_noalloc", "pt_calib_adamw_pattern", "pt_stream_status",
 ]
 
 
@@ -110,6 +110,8 @@ def lib():
         L.pt_chunk_grad_sqnorm_noalloc.argtypes = [vp, C.c_int, u64, u32, C.c_double, vp, vp, vp]
         L.pt_chunk_adamw_step.argtypes = [vp, C.POINTER(pt_hparams), u32, u32, pp, pp, pp, pp, pp, vp]
         L.pt_stream_reserve.argtypes = [vp, u32]
+        L.pt_stream_status.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                       C.POINTER(C.c_int32)]
         L.pt_chunk_stream_step.argtypes = [vp, C.POINTER(pt_hparams), u32, u32, pp, pp, pp, pp, pp, vp]
         L.pt_step_end.argtypes = [vp, vp]
         L.pt_chunk_host_adamw_step.argtypes = [vp, C.POINTER(pt_hparams), u32, u32, pp, pp, pp, pp, pp, u32, vp]
@@ -266,6 +268,15 @@ def pt_chunk_adamw_step(ctx, hp: pt_hparams, first_chunk: int, n_chunks: int, gr
 
 def pt_stream_reserve(ctx, n_slots: int):
     _check(lib().pt_stream_reserve(ctx, int(n_slots)), "pt_stream_reserve", ctx)
+
+
+def pt_stream_status(ctx):
+    """-> dict(duplex_tested, duplex_ok, attempts, rebuilds): outcome of pt_stream_reserve's test of its copy
+    streams, and how often a serialised step has made pt_chunk_stream_step replace the side streams since."""
+    a, b, c, d = C.c_int32(), C.c_int32(), C.c_int32(), C.c_int32()
+    _check(lib().pt_stream_status(ctx, C.byref(a), C.byref(b), C.byref(c), C.byref(d)), "pt_stream_status", ctx)
+    return {"duplex_tested": bool(a.value), "duplex_ok": bool(b.value), "attempts": int(c.value),
+            "rebuilds": int(d.value)}
 
 
 def pt_chunk_stream_step(ctx, hp: pt_hparams, first_chunk: int, n_chunks: int, h_grad, h_master, h_m, h_v,

@@ -133,6 +133,19 @@ struct pt_ctx {
   hipStream_t s_up = nullptr, s_comp = nullptr, s_down = nullptr;
   hipEvent_t ev_fork = nullptr;
   hipEvent_t ev_up[PT_MAX_SLOTS] = {}, ev_k[PT_MAX_SLOTS] = {}, ev_down[PT_MAX_SLOTS] = {};
+  // outcome of the duplex self-test of pt_stream_reserve: tested (the chunk buffers were large enough and the
+  // scratch could be pinned), ok (upload and offload overlapped), offload streams tried
+  uint32_t opt_force_unhealthy = 0;     // tests: the next look at a finished step finds it serialised whatever it measured
+  uint32_t stream_rebuilds = 0;         // times the side streams were replaced after a serialised step
+  void* h_trial = nullptr;              // pinned scratch of the trial copies (kept while chunk buffers are reserved)
+  double link_one_dir_Bps = 0.0;        // one-direction rate of the link, from the reservation's trial copies
+  hipEvent_t ev_t0 = nullptr, ev_t1 = nullptr;   // first upload may start / last offload done (timed)
+  bool health_pending = false;
+  uint64_t health_bytes = 0;            // bytes per direction of the step the two events bracket
+  uint32_t health_chunks = 0;
+  uint32_t opt_duplex_reject = 0;       // the self-test rejects that many offload streams whatever it measures (tests)
+  bool duplex_tested = false, duplex_ok = false;
+  uint32_t duplex_attempts = 0;
   bool slot_used[PT_MAX_SLOTS] = {};
   bool stream_pending = false;
   uint32_t last_slot = 0;
@@ -144,7 +157,7 @@ struct pt_ctx {
   std::vector<uint64_t> h_nd_ranges;
 
   // host-side update: a side stream and a pinned landing buffer for the step's scalars
-  hipStream_t s_scalar = nullptr;
+  PtDevState* h_state_dev = nullptr;    // h_state as the device addresses it (the scalar kernels mirror the state there)
   hipEvent_t ev_scalar = nullptr;
   PtDevState* h_state = nullptr;
   pt_host::Pool* host_pool = nullptr;   // worker threads of the host-side update, started on first use

@@ -94,7 +94,6 @@ extern "C" const char* pt_last_error(const pt_ctx* ctx) {
 static void ctx_free_all(pt_ctx* ctx) {
   pt_host_pool_destroy(ctx);
   pt_stream_release(ctx);
-  if (ctx->s_scalar) (void)hipStreamDestroy(ctx->s_scalar);
   if (ctx->ev_scalar) (void)hipEventDestroy(ctx->ev_scalar);
   if (ctx->h_state) (void)hipHostFree(ctx->h_state);
   if (ctx->d_nd_begin) (void)hipFree(ctx->d_nd_begin);
@@ -124,9 +123,10 @@ static int ctx_alloc(pt_ctx* ctx, const pt_scaler_cfg* sc) {
   size_t np = size_t(ctx->C) * ctx->norm_blocks;
   PT_HIP(ctx, hipMalloc(&ctx->d_norm_part, np * sizeof(double)));
   PT_HIP(ctx, hipMalloc(&ctx->d_norm_flag, np * sizeof(uint32_t)));
-  PT_HIP(ctx, hipStreamCreateWithFlags(&ctx->s_scalar, hipStreamNonBlocking));
   PT_HIP(ctx, hipEventCreateWithFlags(&ctx->ev_scalar, hipEventDisableTiming));
   PT_HIP(ctx, hipHostMalloc((void**)&ctx->h_state, sizeof(PtDevState), hipHostMallocDefault));
+  std::memset(ctx->h_state, 0, sizeof(PtDevState));
+  PT_HIP(ctx, hipHostGetDevicePointer((void**)&ctx->h_state_dev, ctx->h_state, 0));
   double init = sc ? sc->init_scale : 1.0;
   hipLaunchKernelGGL(k_init_state, dim3(1), dim3(1), 0, nullptr, ctx->d_state, init,
                      sc ? sc->growth : 1.0, sc ? sc->backoff : 1.0,
@@ -213,6 +213,15 @@ extern "C" int pt_ctx_set_option(pt_ctx* ctx, const char* name, int64_t value) {
   if (std::strcmp(name, "adamw_threads") == 0) {
     if (value != 0 && value != 256 && value != 512) return pt_fail(ctx, PT_ERR_INVALID_ARG, "adamw_threads must be 0, 256 or 512");
     ctx->opt_adamw_threads = uint32_t(value);
+    return PT_OK;
+  }
+  if (std::strcmp(name, "stream_test_unhealthy") == 0) {
+    ctx->opt_force_unhealthy = value != 0;
+    return PT_OK;
+  }
+  if (std::strcmp(name, "stream_test_reject") == 0) {
+    if (value < 0 || value > 5) return pt_fail(ctx, PT_ERR_INVALID_ARG, "stream_test_reject must be in [0, 5]");
+    ctx->opt_duplex_reject = uint32_t(value);
     return PT_OK;
   }
   if (std::strcmp(name, "pack_tile_elems") == 0) {

@@ -43,11 +43,12 @@ extern "C" int pt_chunk_host_adamw_step(pt_ctx* ctx, const pt_hparams* hp, uint3
   // bits.  Only the scalar kernels are waited for, not the bulk work queued behind them.
   int rc = pt_prepare_consts(ctx, hp, st);
   if (rc != PT_OK) return rc;
-  // ev_scalar was recorded right behind the scalar kernel of this step (pt_prepare_consts)
-  PT_HIP(ctx, hipStreamWaitEvent(ctx->s_scalar, ctx->ev_scalar, 0));
-  PT_HIP(ctx, hipMemcpyAsync(ctx->h_state, ctx->d_state, sizeof(PtDevState), hipMemcpyDeviceToHost, ctx->s_scalar));
-  PT_HIP(ctx, hipStreamSynchronize(ctx->s_scalar));
-  const PtDevState& hs = *ctx->h_state;
+  // ev_scalar was recorded right behind the scalar kernel of this step (pt_prepare_consts), which left a copy
+  // of the scalars in pinned host memory: waiting for that event is all it takes - no stream of the library's
+  // own, whose copy could end up behind the resident update in a shared hardware queue
+  PT_HIP(ctx, hipEventSynchronize(ctx->ev_scalar));
+  PtDevState hs;
+  std::memcpy(&hs, ctx->h_state, sizeof hs);
   if (hs.skip) return PT_OK;                     // skipped step: the host arrays stay as they are
   pt_host::Job job;
   job.k = pt_host::Consts{hs.c[0], hs.c[1], hs.c[2], hs.c[3], hs.c[4], hs.c[5], hs.c[6], hs.c[7], hs.c[8]};

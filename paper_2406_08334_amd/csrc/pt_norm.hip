@@ -218,9 +218,14 @@ __device__ __forceinline__ void prepare_body(PtDevState* st, const pt_hparams& h
   st->skip = st->found_inf ? 1 : 0;
 }
 
-__global__ void k_prepare(PtDevState* st, pt_hparams hp) {
+// `mirror`: a copy of the step's scalars in pinned host memory that the device addresses directly.  The
+// host-side update reads its constants there after waiting for the event behind this kernel - no stream, no
+// copy, nothing that could queue up behind the resident update.
+__global__ void k_prepare(PtDevState* st, pt_hparams hp, PtDevState* mirror) {
   if (threadIdx.x != 0 || blockIdx.x != 0) return;
   prepare_body(st, hp);
+  *mirror = *st;
+  __threadfence_system();
 }
 
 // The scalar work of a step in ONE launch, for small states where launches are what a step costs:
@@ -232,7 +237,7 @@ __global__ void __launch_bounds__(NB_THREADS)
 k_reduce_finalize_prepare(const double* __restrict__ part, const uint32_t* __restrict__ flag,
                           const uint32_t* __restrict__ tile_begin, uint32_t first, uint32_t n_reduce, uint32_t per_chunk,
                           double* chunk_sq, uint32_t* chunk_flag, uint32_t C, PtDevState* st, pt_hparams hp,
-                          int do_finalize, int do_prepare) {
+                          int do_finalize, int do_prepare, PtDevState* mirror) {
   for (uint32_t i = 0; i < n_reduce; ++i) {
     const uint32_t c = first + i;
     uint32_t lo, hi;
@@ -248,7 +253,11 @@ k_reduce_finalize_prepare(const double* __restrict__ part, const uint32_t* __res
   if (threadIdx.x != 0) return;
   // thread 0 wrote every per-chunk value of this launch itself; the others come from earlier kernels
   if (do_finalize) finalize_body(chunk_sq, chunk_flag, C, st);
-  if (do_prepare) prepare_body(st, hp);
+  if (do_prepare) {
+    prepare_body(st, hp);
+    *mirror = *st;
+    __threadfence_system();
+  }
 }
 
 }  // namespace
@@ -316,12 +325,12 @@ int pt_prepare_consts(pt_ctx* ctx, const pt_hparams* hp, hipStream_t stream) {
     hipLaunchKernelGGL(k_reduce_finalize_prepare, dim3(1), dim3(NB_THREADS), 0, stream, red ? r.part : nullptr,
                        red ? r.flag : nullptr, red ? r.tile_begin : nullptr, red ? r.first : 0u, red ? r.n : 0u,
                        red ? r.per_chunk : 0u, ctx->d_chunk_sq, ctx->d_chunk_flag, ctx->C, ctx->d_state, *hp,
-                       ctx->pend_finalize ? 1 : 0, 1);
+                       ctx->pend_finalize ? 1 : 0, 1, ctx->h_state_dev);
     PT_LAUNCH_CHECK(ctx, "k_reduce_finalize_prepare");
     ctx->pend_reduce.active = false;
     ctx->pend_finalize = false;
   } else {
-    hipLaunchKernelGGL(k_prepare, dim3(1), dim3(1), 0, stream, ctx->d_state, *hp);
+    hipLaunchKernelGGL(k_prepare, dim3(1), dim3(1), 0, stream, ctx->d_state, *hp, ctx->h_state_dev);
     PT_LAUNCH_CHECK(ctx, "k_prepare");
   }
   PT_HIP(ctx, hipEventRecord(ctx->ev_scalar, stream));   // lets the host-side update read the scalars early

@@ -9,6 +9,7 @@
 //   ptchunk_probe [chunk_elems=67108864] [n_chunks=101] [steps=3] [copies=4]
 #include <hip/hip_runtime.h>
 
+#include <chrono>
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
@@ -131,8 +132,42 @@ int main(int argc, char** argv) {
       memcpy(hgp[i], hg.data(), 2 * S); memcpy(hpp[i], hp.data(), 2 * S); memcpy(hwp[i], hw.data(), 4 * S);
       memset(hmp[i], 0, 4 * S); memset(hvp[i], 0, 4 * S);
     }
+    // what the link gives bare copies of the same pinned arrays (one 4*S-byte array per copy, no kernels): one
+    // direction at a time, then both at once on two streams - the rates the streamed step is measured against
+    {
+      void *d_up = nullptr, *d_dn = nullptr;
+      hipStream_t sa, sb;
+      CHECK_HIP(hipMalloc(&d_up, 4 * S)); CHECK_HIP(hipMalloc(&d_dn, 4 * S));
+      CHECK_HIP(hipMemset(d_dn, 0, 4 * S));                 // what comes down is what the host arrays hold anyway
+      CHECK_HIP(hipStreamCreateWithFlags(&sa, hipStreamNonBlocking)); CHECK_HIP(hipStreamCreateWithFlags(&sb, hipStreamNonBlocking));
+      CHECK_HIP(hipDeviceSynchronize());
+      auto run = [&](bool up, bool down, double* gbps) -> int {
+        CHECK_HIP(hipDeviceSynchronize());
+        const auto t0 = std::chrono::steady_clock::now();
+        for (uint32_t i = 0; i < n_host; ++i) {
+          if (up) CHECK_HIP(hipMemcpyAsync(d_up, hwp[i], 4 * S, hipMemcpyHostToDevice, sa));
+          if (down) CHECK_HIP(hipMemcpyAsync(hvp[i], d_dn, 4 * S, hipMemcpyDeviceToHost, sb));
+        }
+        CHECK_HIP(hipDeviceSynchronize());
+        const double sec = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+        *gbps = 4.0 * double(S) * n_host / sec / 1e9;
+        return 0;
+      };
+      double warm, h2d, d2h, both;
+      if (run(true, true, &warm) || run(true, false, &h2d) || run(false, true, &d2h) || run(true, true, &both)) return 1;
+      printf("bare pinned copies, %u x %llu bytes: H2D alone %.2f GB/s, D2H alone %.2f GB/s, both at once %.2f GB/s per direction\n",
+             n_host, (unsigned long long)(4 * S), h2d, d2h, both);
+      CHECK_HIP(hipStreamDestroy(sa)); CHECK_HIP(hipStreamDestroy(sb));
+      CHECK_HIP(hipFree(d_up)); CHECK_HIP(hipFree(d_dn));
+    }
     const uint32_t slots = getenv("PROBE_SLOTS") ? (uint32_t)atoi(getenv("PROBE_SLOTS")) : 3;
     CHECK_PT(ctx, pt_stream_reserve(ctx, slots));
+    {
+      int32_t tested = 0, ok = 0, attempts = 0;
+      CHECK_PT(ctx, pt_stream_status(ctx, &tested, &ok, &attempts, nullptr));
+      printf("copy streams: duplex test %s, %s, %d stream pair(s) tried\n", tested ? "run" : "not run",
+             ok ? "upload and offload overlap" : "no overlap seen", attempts);
+    }
     for (int s = 0; s < steps; ++s) {
       CHECK_HIP(hipEventRecord(e[0], st));
       CHECK_PT(ctx, pt_chunk_pack_grads(ctx, plan, g.data(), st));
@@ -144,8 +179,10 @@ int main(int argc, char** argv) {
       CHECK_HIP(hipStreamSynchronize(st));
       float t;
       CHECK_HIP(hipEventElapsedTime(&t, e[0], e[1]));
-      printf("streamed step %d: %u resident + %u host chunks, %u slots: %.2f ms, %.2f GB/s per direction\n", s, C, n_host, slots, t,
-             14.0 * double(S) * n_host / t / 1e6);
+      int32_t rebuilds = 0;
+      CHECK_PT(ctx, pt_stream_status(ctx, nullptr, nullptr, nullptr, &rebuilds));
+      printf("streamed step %d: %u resident + %u host chunks, %u slots: %.2f ms, %.2f GB/s per direction (side streams replaced %d time(s) so far)\n",
+             s, C, n_host, slots, t, 14.0 * double(S) * n_host / t / 1e6, rebuilds);
     }
   }
   // PROBE_ACCUM=<k> [PROBE_ZERO=1]: the gradient-accumulation variant on the same state: a second context

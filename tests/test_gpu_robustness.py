@@ -7,6 +7,7 @@ import pytest
 import torch
 
 from paper_2406_08334_amd import binding as B
+from paper_2406_08334_amd import synth
 
 from gpu_harness import ChunkedState, hp_pair, to_u16, same_bits, assert_same_bits
 
@@ -195,3 +196,73 @@ def test_two_contexts_on_two_streams_do_not_disturb_each_other(orc):
     finally:
         for st in solo + duo:
             st.close()
+
+
+def test_stream_reserve_tries_its_copy_streams_out_and_ends_with_a_pair_that_overlaps():
+    """A stream keeps the copy engine of its first copy, and two copy streams that took the same one carry one
+    direction of the link at a time.  pt_stream_reserve makes the first copies itself, side by side, then measures
+    (one copy up, one down, both at once) and replaces a pair that does not overlap.  Here: a process that has created
+    and destroyed other streams right before, several contexts in a row - every reservation must end with an
+    overlapping pair; the replacement forced from the host; and small chunk buffers, which skip the test."""
+    S = 1 << 22                                   # 64 MiB chunk buffers: large enough to measure
+    ctxs = []
+    try:
+        for k in range(3):
+            junk = [torch.cuda.Stream() for _ in range(k + 1)]
+            for s in junk:
+                with torch.cuda.stream(s):
+                    torch.zeros(8, device="cuda")
+            torch.cuda.synchronize()
+            del junk
+            ctx = B.pt_ctx_create(B.PT_BF16, S, 4, None)
+            ctxs.append(ctx)
+            B.pt_stream_reserve(ctx, 2)
+            st = B.pt_stream_status(ctx)
+            print(f"[stream self-test] context {k}: {st}", flush=True)
+            assert st["duplex_tested"] and st["duplex_ok"] and 1 <= st["attempts"] <= 6, st
+        # the replacement itself, forced from the host: two stream pairs rejected whatever they measure, the third
+        # kept; the streamed update through the replaced stream still gives the resident bits
+        forced = B.pt_ctx_create(B.PT_BF16, S, 4, None)
+        ctxs.append(forced)
+        B.pt_ctx_set_option(forced, "stream_test_reject", 2)
+        B.pt_stream_reserve(forced, 2)
+        st = B.pt_stream_status(forced)
+        assert st["duplex_tested"] and st["duplex_ok"] and st["attempts"] == 3, st
+        hp_b, _, _ = hp_pair()
+        dev = {k: torch.zeros(2, S, dtype=dt, device="cuda") for k, dt in
+               (("g", torch.bfloat16), ("p", torch.bfloat16), ("w", torch.float32), ("m", torch.float32), ("v", torch.float32))}
+        synth.normal_16(synth.SEED_GRADS, 1, 0, 0, 2 * S, 1e-3, torch.bfloat16, "cuda", out=dev["g"].view(-1))
+        synth.normal_16(synth.SEED_PARAMS, 0, 0, 0, 2 * S, 0.02, torch.bfloat16, "cuda", out=dev["p"].view(-1))
+        dev["w"].copy_(dev["p"])
+        host = {k: [t[c].cpu().pin_memory() for c in range(2)] for k, t in dev.items()}
+        rows = lambda k: [dev[k][0], dev[k][1]]
+
+        def step_and_compare(tag):
+            B.pt_chunk_grad_sqnorm(forced, [dev["g"][0], dev["g"][1], None, None], 0, 2, False)
+            B.pt_chunk_grad_sqnorm(forced, None, 0, 4, B.PT_FINALIZE_CARRY)
+            B.pt_chunk_stream_step(forced, hp_b, 2, 2, host["g"], host["w"], host["m"], host["v"], host["p"])
+            B.pt_chunk_adamw_step(forced, hp_b, 0, 2, rows("g"), rows("w"), rows("m"), rows("v"), rows("p"))
+            B.pt_step_end(forced)
+            torch.cuda.synchronize()
+            for k in ("w", "m", "v", "p"):
+                for c in range(2):
+                    view = torch.int16 if k == "p" else torch.int32
+                    assert torch.equal(host[k][c].view(view), dev[k][c].cpu().view(view)), (tag, k, c)
+        step_and_compare("first step")
+        assert B.pt_stream_status(forced)["rebuilds"] == 0
+        # A step that ran with its two directions behind each other makes the next call replace the side streams;
+        # here the verdict on the finished step is forced from the host.  Same bits through the new streams.
+        B.pt_ctx_set_option(forced, "stream_test_unhealthy", 1)
+        step_and_compare("step after the verdict")
+        st = B.pt_stream_status(forced)
+        assert st["rebuilds"] == 1 and st["duplex_tested"], st
+        step_and_compare("a further step")
+        assert B.pt_stream_status(forced)["rebuilds"] == 1
+        small = B.pt_ctx_create(B.PT_BF16, 4096, 2, None)
+        ctxs.append(small)
+        B.pt_stream_reserve(small, 2)
+        assert B.pt_stream_status(small) == {"duplex_tested": False, "duplex_ok": False, "attempts": 0, "rebuilds": 0}
+    finally:
+        torch.cuda.synchronize()
+        for ctx in ctxs:
+            B.pt_ctx_destroy(ctx)
