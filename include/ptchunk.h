@@ -321,11 +321,13 @@ int pt_chunk_adamw_step(pt_ctx* ctx, const pt_hparams* hp, uint32_t first_chunk,
 /* Device chunk buffers for the streamed path (paper: pre-allocated chunk buffers
  * for non-persistent chunks).  Allocates n_slots buffers of 16 bytes x chunk_elems,
  * three side streams and the events.  n_slots >= 2.  Not a hot call.
+ * The side streams it keeps are the second three it makes (the first three are given up once the others
+ * exist): the first streams a process makes were measured to share hardware queues with the caller's
+ * stream, later ones to find queues of their own.
  * With chunk buffers of 32 MiB or more it also makes the first copies of the upload and the offload stream
  * itself, side by side (a stream keeps the copy engine of its first copy, and two streams that took the same
  * one carry one direction of the link at a time), then measures one copy up, one down and both at once
- * through the first buffer and a pinned scratch that is freed again; a pair that does not overlap is replaced,
- * up to five times.  Skipped when the scratch (at most 128 MiB, kept until the context goes) cannot be pinned. */
+ * through the first buffer and a pinned scratch; a pair that does not overlap is replaced, up to five times.  Skipped when the scratch (at most 128 MiB, kept until the context goes) cannot be pinned. */
 int pt_stream_reserve(pt_ctx* ctx, uint32_t n_slots);
 
 /* Outcome of that test: duplex_tested 0 = not run; duplex_ok 1 = upload and offload overlapped; attempts =
@@ -366,9 +368,9 @@ int pt_chunk_stream_step(pt_ctx* ctx, const pt_hparams* hp, uint32_t first_chunk
 /* Update of host-resident chunks ON THE HOST: the paper's own placement (CPU Adam for
  * non-persistent chunks, running concurrently with GPU work; "Hierarchical Chunk Management for
  * Model States", Appendix A.1 T_CPU_OPTIM).  Same arithmetic and the same nine fp32 constants
- * as pt_chunk_adamw_step - the constants are read back from the device, waiting only for the
- * scalar kernels already queued on `stream`, not for bulk work behind them - so results are
- * bit-identical to the device paths.  BLOCKING: returns when n_threads host threads (this one
+ * as pt_chunk_adamw_step - the scalar kernel of the step leaves them in pinned host memory as
+ * well, and the call waits for the event behind that kernel only, not for bulk work queued after
+ * it - so results are bit-identical to the device paths.  BLOCKING: returns when n_threads host threads (this one
  * included) have updated master, m, v and param16 of chunks [first_chunk, first_chunk+n_chunks)
  * in place.  Queue pt_chunk_adamw_step for the resident chunks first and the two run side by
  * side.  h_*: host arrays of n_chunks host pointers (pinned or not).  A skipped step leaves the
