@@ -360,7 +360,8 @@ int pt_stream_status(const pt_ctx* ctx, int32_t* duplex_tested, int32_t* duplex_
  * single copies for that; and each call here first reads two timed events that bracketed the previous
  * streamed step (if they are done: it never waits): a step that moved less than 0.65 of the link's
  * one-direction rate had its directions behind each other, and the call then replaces the three side
- * streams by new ones before it enqueues anything (at most four times per context; pt_stream_status). */
+ * streams by new ones before it enqueues anything (at most four times per context; pt_stream_status).
+ * That one call tries the new streams out and synchronises the device; every other call only enqueues. */
 int pt_chunk_stream_step(pt_ctx* ctx, const pt_hparams* hp, uint32_t first_chunk, uint32_t n_chunks,
                          const void* const* h_grad, float* const* h_master, float* const* h_m,
                          float* const* h_v, void* const* h_param16, void* stream);
